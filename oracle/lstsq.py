@@ -55,10 +55,15 @@ def back_substitute(R: np.ndarray, Z: np.ndarray) -> np.ndarray:
     return B
 
 
-def rank_check(R11: np.ndarray, n_rows: int) -> None:
-    """Numerical rank test on the diagonal of R (H^T H must be invertible)."""
+def rank_check(R11: np.ndarray) -> None:
+    """Numerical rank test on the diagonal of R (H^T H must be invertible).
+
+    H is treated as rank deficient when min|R_jj| <= eps32 * max|R_jj|: the
+    device path factors in float32, so a diagonal ratio at float32 rounding
+    level cannot be told from zero there.
+    """
     dg = np.abs(np.diag(R11))
-    if dg.min() <= n_rows * np.finfo(np.float32).eps * dg.max():
+    if dg.min() <= np.finfo(np.float32).eps * dg.max():
         raise RankDeficient("H is numerically rank deficient")
 
 
@@ -79,7 +84,7 @@ def solve(H: np.ndarray, T: np.ndarray, check_rank: bool = True):
     R11 = np.triu(A[:L, :L])
     R12 = A[:L, L:]
     if check_rank:
-        rank_check(R11, N)
+        rank_check(R11)
     beta = back_substitute(R11, R12)
     rss = float(np.sum(A[L:, L:] ** 2))
     return beta, rss, A[:L, :].copy()
@@ -113,7 +118,7 @@ def solve_chunked(H: np.ndarray, T: np.ndarray, chunk: int = 4096, check_rank: b
         raise ValueError("N must be at least L")
     R11 = np.triu(carry[:, :L])
     if check_rank:
-        rank_check(R11, N)
+        rank_check(R11)
     beta = back_substitute(R11, carry[:, L:])
     return beta, rss, carry.copy()
 
