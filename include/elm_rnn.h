@@ -1,0 +1,167 @@
+/*
+ * elm_rnn.h -- C ABI of the MI355X (gfx950) ELM-RNN fit library.
+ *
+ * Non-iterative training of a recurrent network (the paper's Algorithm
+ * "S-R-ELM"): (1) input, recurrent and bias weights are drawn once from a seed
+ * and frozen; (2) every training window is unrolled over Q steps through the
+ * cell and its final hidden state becomes one row of H (N x L); (3) the output
+ * weights are beta = H^+ T, computed here as the least-squares solution by a
+ * Householder tall-skinny QR of [H | T] and a triangular back-solve (the
+ * paper's section "Computing beta").
+ *
+ * General conventions
+ *   - Every function returns 0 (ELM_OK) or a negative error code; nothing
+ *     throws across this boundary.  elm_rnn_strerror() names a code and
+ *     elm_rnn_last_hip_error() returns the text of the last HIP failure.
+ *   - "device" pointers are HIP device memory on the current device, owned by
+ *     the caller; the library never frees them and allocates no O(N) memory.
+ *     "host" pointers are ordinary memory.  A model owns only its small weight
+ *     and beta buffers on the device.
+ *   - All work is enqueued on the caller's stream (hip_stream: a hipStream_t
+ *     cast to void*, NULL = the default stream).  Functions that return values
+ *     to the host (stats) synchronise that stream before returning.
+ *   - Matrices are row-major float32 unless stated.  X[i, t, :] (sample i, step
+ *     t, d contiguous channels) lives at X + i*ldx_n + t*ldx_q (strides in
+ *     elements): materialised windows use ldx_n = Q*d, ldx_q = d; zero-copy
+ *     sliding windows over a series use ldx_n = stride*d, ldx_q = d.  This is
+ *     the paper's n x S x Q input with the step axis moved before the feature
+ *     axis so that one step of one sample is contiguous.
+ *   - Weight layout: W is d x kL, U is L x kL, b is kL with k gate blocks side
+ *     by side: Elman k = 1; LSTM k = 4 in the order (i, f, o, g) = the paper's
+ *     (in, lambda, o, candidate); GRU k = 3 in the order (z, r, n).
+ *   - Supported sizes: 1 <= L <= 512, 1 <= d <= 64, 1 <= m <= 16, N >= 1.
+ */
+#ifndef ELM_RNN_H
+#define ELM_RNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ELM_CELL_ELMAN 0   /* h_t = tanh(x_t W + h_{t-1} U + b): dense lag-1 form of the paper's
+                              "Fully Connected RNN" / "Elman" recurrences                        */
+#define ELM_CELL_LSTM  1   /* the paper's section "LSTM" (no peepholes)                          */
+#define ELM_CELL_GRU   2   /* the paper's section "GRU": f = (1-z) f_prev + z tanh(W x + U (r f_prev) + b) */
+
+#define ELM_OK            0
+#define ELM_EINVAL       -1   /* null pointer, non-positive size, unknown cell, N < L for a solve */
+#define ELM_EWORKSPACE   -2   /* workspace pointer null or smaller than the *_workspace_bytes()   */
+#define ELM_ERANK        -3   /* H numerically rank deficient: min|R_jj| <= eps32 * max|R_jj|;
+                                 beta is still written but must not be trusted                   */
+#define ELM_EHIP         -4   /* a HIP call failed; see elm_rnn_last_hip_error()                  */
+#define ELM_EUNSUPPORTED -5   /* size outside the supported range listed above                    */
+
+typedef struct elm_rnn_model elm_rnn_model;   /* opaque; from *_create or fit, released by elm_rnn_free */
+
+/* How step (1) of Algorithm "S-R-ELM" draws the weights ("Randomly assign W, alpha, b").
+ * A SplitMix64 stream seeded with `seed` yields u in [0,1) with 53 bits; each value is
+ * (2u-1)*w_scale in double; draw order W (row-major), U (row-major), b; then
+ *   spectral_radius > 0 (Elman only): U *= spectral_radius / max|eig(U)|
+ *   zero_bias != 0: b = 0 (the draws are still consumed), else
+ *   LSTM: forget_bias is added to the forget block of b;
+ * finally everything is rounded to float32. */
+typedef struct {
+    double w_scale;
+    double spectral_radius;
+    double forget_bias;
+    int    zero_bias;
+} elm_rnn_init;
+
+/* Filled by elm_rnn_solve / elm_rnn_fit (host memory). */
+typedef struct {
+    double t_hidden_ms;   /* stage 1 (hidden-matrix build), device time; 0 from elm_rnn_solve     */
+    double t_solve_ms;    /* stage 2 (TSQR + back-solve + refinement), device time                */
+    double rmse;          /* sqrt(sum (H beta - T)^2 / (N m)) of the returned beta, from a float64
+                             residual pass over H                                                 */
+    double rmse_qr;       /* the same quantity read off the float32 R factor: ||R22||_F/sqrt(N m) */
+    double ne_resid;      /* ||H^T (H beta - T)||_F / (||H||_F ||H beta - T||_F), float64          */
+    double r_diag_min;    /* min and max |R_jj| over the L columns of H (condition indicator)      */
+    double r_diag_max;
+    int    refine_iters;  /* float64-residual refinement steps applied to beta                     */
+} elm_rnn_stats;
+
+/* ---- step (1): weights -------------------------------------------------------------------- */
+
+/* Draw the weights for (cell, d, L) from `seed` on the host as described at elm_rnn_init, and
+ * upload them.  Q is the default number of steps, m the number of outputs (beta is L x m, zero
+ * until a fit stores it).  *model_out receives the new model. */
+int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
+                         const elm_rnn_init* init, elm_rnn_model** model_out);
+
+/* Same, but with caller-supplied float32 host weights W[d*kL], U[L*kL], b[kL] (copied). */
+int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m,
+                                      const float* W, const float* U, const float* b,
+                                      elm_rnn_model** model_out);
+
+/* Copy the model's weights to host arrays (any of W, U, b, beta64 may be NULL).  beta64 is the
+ * L x m float64 output-weight matrix.  Synchronous. */
+int elm_rnn_get_weights(const elm_rnn_model* model, float* W, float* U, float* b, double* beta64);
+
+/* Store output weights (host, L x m float64) into the model, e.g. to predict with a loaded beta. */
+int elm_rnn_set_beta(elm_rnn_model* model, const double* beta64);
+
+void elm_rnn_free(elm_rnn_model* model);
+
+/* ---- step (2): H(Q) ------------------------------------------------------------------------ */
+
+/* Unroll N windows through the model's cell for Q_run steps (1 <= Q_run; X must hold that many
+ * steps) and write the final hidden state of sample i to H_out[i*L .. i*L+L) (device).  h0 / c0
+ * (device, N x L, nullable = zero) give the state before the first step; c0 and c_out (nullable)
+ * are used by the LSTM only.  Only H(Q) is produced: the per-step states never leave the chip
+ * (step 3 of Algorithm "S-R-ELM" uses H(Q) alone). */
+int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
+                   int64_t N, int Q_run, const float* h0, const float* c0,
+                   float* H_out, float* c_out, void* hip_stream);
+
+/* ---- step (3): beta = H^+ T ---------------------------------------------------------------- */
+
+/* Device workspace elm_rnn_solve needs for an N x L system with m right-hand sides. */
+size_t elm_rnn_solve_workspace_bytes(int64_t N, int L, int m);
+
+/* Least squares min ||H beta - T||_F for device H (N x L) and T (N x m), N >= L.
+ * Blocked Householder TSQR of [H | T] in float32 (the paper's H = QR, z = Q^T Y), back
+ * substitution R beta = z, then `refine` (0..4; the library default is 2) steps of iterative
+ * refinement whose residual T - H beta and gradient H^T r are accumulated in float64.
+ * beta_out (device, L x m float32) and beta64_out (device, L x m float64, nullable) receive
+ * the result; stats (host, nullable) is filled after a stream synchronisation.
+ * Returns ELM_ERANK (after writing outputs) if H is numerically rank deficient. */
+int elm_rnn_solve(const float* H, const float* T, int64_t N, int L, int m, int refine,
+                  float* beta_out, double* beta64_out, elm_rnn_stats* stats,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- the whole fit -------------------------------------------------------------------------- */
+
+/* Workspace for elm_rnn_fit: the solve workspace, plus N*L floats when H_out is NULL. */
+size_t elm_rnn_fit_workspace_bytes(int64_t N, int L, int m, int h_in_workspace);
+
+/* Algorithm "S-R-ELM" end to end: create the model from `seed`, build H(Q) from the device
+ * windows X, solve for beta against the device targets T (N x m), keep beta in the model.
+ * H_out (device, N x L) is nullable (then H lives in the workspace).  beta_out / beta64_out /
+ * stats as in elm_rnn_solve.  *model_out receives the model (also on ELM_ERANK). */
+int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T,
+                int64_t N, int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
+                void* workspace, size_t workspace_bytes, void* hip_stream,
+                float* H_out, float* beta_out, double* beta64_out,
+                elm_rnn_stats* stats, elm_rnn_model** model_out);
+
+/* Workspace for elm_rnn_predict: N*L floats for H. */
+size_t elm_rnn_predict_workspace_bytes(int64_t N, int L);
+
+/* The paper's output equation y_hat = sum_i beta_i f_i(Q): build H(Q) for N new windows with
+ * the model's weights and write Y_out = H beta (device, N x m float32). */
+int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
+                    int64_t N, float* Y_out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* ---- diagnostics ---------------------------------------------------------------------------- */
+
+const char* elm_rnn_strerror(int code);
+const char* elm_rnn_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELM_RNN_H */

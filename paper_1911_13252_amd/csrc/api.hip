@@ -1,0 +1,356 @@
+// C ABI of libelmrnn: argument checks, the seeded weight generator (step 1 of the paper's
+// Algorithm "S-R-ELM"), model life-cycle and the orchestration of stage 1 and stage 2.
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "internal.h"
+
+struct elm_rnn_model {
+    int cell, Q, d, L, m, G;
+    elm::PackedLayout lay;
+    std::vector<float> W, U, b;   // host copies, float32
+    float* dWp = nullptr;         // packed [U; W; b] on the device
+    double* dBeta = nullptr;      // L x m float64 on the device
+};
+
+namespace elm {
+
+static thread_local char g_hip_error[512] = "";
+
+void set_hip_error(hipError_t e, const char* where) {
+    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", where, hipGetErrorString(e));
+}
+
+namespace {
+
+// SplitMix64 (Steele, Lea, Flood: "Fast splittable pseudorandom number generators").
+struct SplitMix64 {
+    uint64_t state;
+    explicit SplitMix64(uint64_t seed) : state(seed) {}
+    uint64_t next() {
+        state += 0x9E3779B97F4A7C15ull;
+        uint64_t z = state;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    double uniform() { return (double)(next() >> 11) * 0x1.0p-53; }
+};
+
+double frobenius(const std::vector<double>& a) {
+    double s = 0.0;
+    for (double v : a) s += v * v;
+    return std::sqrt(s);
+}
+
+// Spectral radius by Gelfand's formula rho = lim ||A^k||^(1/k) along k = 2^i with renormalised
+// repeated squaring: A^(2^i) = exp(2^i s_i) B_i, ||B_i||_F = 1, s_{i+1} = s_i + 2^-(i+1) log||B_i^2||_F.
+double spectral_radius(const std::vector<double>& A, int n) {
+    std::vector<double> B(A), C((size_t)n * n);
+    double nf = frobenius(B);
+    if (nf == 0.0) return 0.0;
+    for (double& v : B) v /= nf;
+    double log_rho = std::log(nf), w = 1.0;
+    for (int it = 0; it < 60; ++it) {
+        std::fill(C.begin(), C.end(), 0.0);
+        for (int i = 0; i < n; ++i)
+            for (int k = 0; k < n; ++k) {
+                const double bik = B[(size_t)i * n + k];
+                const double* brow = &B[(size_t)k * n];
+                double* crow = &C[(size_t)i * n];
+                for (int j = 0; j < n; ++j) crow[j] += bik * brow[j];
+            }
+        const double nc = frobenius(C);
+        if (nc == 0.0) return 0.0;       // nilpotent
+        w *= 0.5;
+        log_rho += w * std::log(nc);
+        for (double& v : C) v /= nc;
+        B.swap(C);
+    }
+    return std::exp(log_rho);
+}
+
+int check_dims(int cell, int Q, int d, int L, int m) {
+    if (cell != ELM_CELL_ELMAN && cell != ELM_CELL_LSTM && cell != ELM_CELL_GRU) return ELM_EINVAL;
+    if (Q < 1 || d < 1 || L < 1 || m < 1) return ELM_EINVAL;
+    if (L > 512 || d > 64 || m > 16) return ELM_EUNSUPPORTED;
+    return ELM_OK;
+}
+
+int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, std::vector<float>&& U,
+                std::vector<float>&& b, elm_rnn_model** out) {
+    elm_rnn_model* mdl = new (std::nothrow) elm_rnn_model();
+    if (mdl == nullptr) return ELM_EINVAL;
+    mdl->cell = cell; mdl->Q = Q; mdl->d = d; mdl->L = L; mdl->m = m; mdl->G = gates_of(cell);
+    mdl->lay = packed_layout(cell, d, L);
+    mdl->W = std::move(W); mdl->U = std::move(U); mdl->b = std::move(b);
+    std::vector<float> packed(mdl->lay.floats);
+    pack_weights(mdl->lay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
+    hipError_t e = hipMalloc(&mdl->dWp, packed.size() * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
+    if (e == hipSuccess)
+        e = hipMemcpy(mdl->dWp, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(mdl->dBeta, 0, (size_t)L * m * sizeof(double));
+    if (e != hipSuccess) {
+        set_hip_error(e, "model upload");
+        elm_rnn_free(mdl);
+        return ELM_EHIP;
+    }
+    *out = mdl;
+    return ELM_OK;
+}
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create() {
+        hipError_t e = hipEventCreate(&a);
+        if (e == hipSuccess) e = hipEventCreate(&b);
+        return e;
+    }
+    ~EventPair() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
+// stage 2 on the stream; fills stats (after a sync) when asked.  hidden_ms is copied through.
+int run_solve(const float* H, const float* T, int64_t N, int L, int m, int refine, float* beta_out,
+              double* beta64_out, elm_rnn_stats* stats, void* ws, size_t ws_bytes,
+              hipStream_t stream, double hidden_ms, hipEvent_t hidden_done) {
+    if (H == nullptr || T == nullptr || beta_out == nullptr) return ELM_EINVAL;
+    if (N < 1 || L < 1 || m < 1 || N < L || refine < 0 || refine > 4) return ELM_EINVAL;
+    if (L > 512 || m > 16) return ELM_EUNSUPPORTED;
+    const SolvePlan plan = make_solve_plan(N, L, m);
+    if (ws == nullptr || ws_bytes < plan.bytes) return ELM_EWORKSPACE;
+
+    EventPair ev;
+    ELM_HIP_TRY(ev.create());
+    if (hidden_done == nullptr) ELM_HIP_TRY(hipEventRecord(ev.a, stream));
+
+    float* R = nullptr;
+    ELM_HIP_TRY(launch_tsqr(plan, H, T, ws, &R, stream));
+    ELM_HIP_TRY(launch_backsolve(plan, R, ws, stream));
+    for (int it = 0; it < refine; ++it) {
+        ELM_HIP_TRY(launch_residual_pass(plan, H, T, ws, stream));
+        ELM_HIP_TRY(launch_refine_update(plan, R, ws, stream));
+    }
+    ELM_HIP_TRY(launch_residual_pass(plan, H, T, ws, stream));     // statistics of the final beta
+    ELM_HIP_TRY(launch_export_beta(plan, ws, beta_out, beta64_out, stream));
+    ELM_HIP_TRY(hipEventRecord(ev.b, stream));
+
+    // the rank flag is always read back: the return code depends on it
+    double sc[8];
+    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(ws) + plan.off_small);
+    ELM_HIP_TRY(hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream));
+    ELM_HIP_TRY(hipStreamSynchronize(stream));
+    if (stats != nullptr) {
+        float ms = 0.0f;
+        ELM_HIP_TRY(hipEventElapsedTime(&ms, hidden_done ? hidden_done : ev.a, ev.b));
+        stats->t_hidden_ms = hidden_ms;
+        stats->t_solve_ms = ms;
+        const double nm = (double)N * m;
+        stats->rmse = std::sqrt(sc[0] / nm);
+        stats->rmse_qr = std::sqrt(sc[3] / nm);
+        const double den = std::sqrt(sc[1]) * std::sqrt(sc[0]);
+        stats->ne_resid = den > 0.0 ? std::sqrt(sc[2]) / den : 0.0;
+        stats->r_diag_min = sc[4];
+        stats->r_diag_max = sc[5];
+        stats->refine_iters = refine;
+    }
+    return sc[6] != 0.0 ? ELM_ERANK : ELM_OK;
+}
+
+}  // namespace
+}  // namespace elm
+
+using namespace elm;
+
+extern "C" {
+
+int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
+                         const elm_rnn_init* init, elm_rnn_model** model_out) {
+    if (init == nullptr || model_out == nullptr) return ELM_EINVAL;
+    int rc = check_dims(cell, Q, d, L, m);
+    if (rc != ELM_OK) return rc;
+    if (!(init->w_scale > 0.0) || init->spectral_radius < 0.0) return ELM_EINVAL;
+    if (init->spectral_radius > 0.0 && cell != ELM_CELL_ELMAN) return ELM_EINVAL;
+    const int G = gates_of(cell), GL = G * L;
+    SplitMix64 rng(seed);
+    std::vector<double> W((size_t)d * GL), U((size_t)L * GL), b((size_t)GL);
+    for (double& v : W) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
+    for (double& v : U) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
+    for (double& v : b) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
+    if (init->spectral_radius > 0.0) {
+        const double rho = spectral_radius(U, L);
+        if (!(rho > 0.0)) return ELM_EINVAL;
+        const double f = init->spectral_radius / rho;
+        for (double& v : U) v *= f;
+    }
+    if (init->zero_bias) {
+        for (double& v : b) v = 0.0;
+    } else if (cell == ELM_CELL_LSTM && init->forget_bias != 0.0) {
+        for (int j = 0; j < L; ++j) b[(size_t)L + j] += init->forget_bias;
+    }
+    std::vector<float> Wf(W.begin(), W.end()), Uf(U.begin(), U.end()), bf(b.begin(), b.end());
+    return build_model(cell, Q, d, L, m, std::move(Wf), std::move(Uf), std::move(bf), model_out);
+}
+
+int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m, const float* W,
+                                      const float* U, const float* b, elm_rnn_model** model_out) {
+    if (W == nullptr || U == nullptr || b == nullptr || model_out == nullptr) return ELM_EINVAL;
+    int rc = check_dims(cell, Q, d, L, m);
+    if (rc != ELM_OK) return rc;
+    const size_t GL = (size_t)gates_of(cell) * L;
+    std::vector<float> Wf(W, W + (size_t)d * GL), Uf(U, U + (size_t)L * GL), bf(b, b + GL);
+    return build_model(cell, Q, d, L, m, std::move(Wf), std::move(Uf), std::move(bf), model_out);
+}
+
+int elm_rnn_get_weights(const elm_rnn_model* model, float* W, float* U, float* b, double* beta64) {
+    if (model == nullptr) return ELM_EINVAL;
+    if (W) std::memcpy(W, model->W.data(), model->W.size() * sizeof(float));
+    if (U) std::memcpy(U, model->U.data(), model->U.size() * sizeof(float));
+    if (b) std::memcpy(b, model->b.data(), model->b.size() * sizeof(float));
+    if (beta64)
+        ELM_HIP_TRY(hipMemcpy(beta64, model->dBeta, (size_t)model->L * model->m * sizeof(double),
+                              hipMemcpyDeviceToHost));
+    return ELM_OK;
+}
+
+int elm_rnn_set_beta(elm_rnn_model* model, const double* beta64) {
+    if (model == nullptr || beta64 == nullptr) return ELM_EINVAL;
+    ELM_HIP_TRY(hipMemcpy(model->dBeta, beta64, (size_t)model->L * model->m * sizeof(double),
+                          hipMemcpyHostToDevice));
+    return ELM_OK;
+}
+
+void elm_rnn_free(elm_rnn_model* model) {
+    if (model == nullptr) return;
+    if (model->dWp) (void)hipFree(model->dWp);
+    if (model->dBeta) (void)hipFree(model->dBeta);
+    delete model;
+}
+
+int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
+                   int64_t N, int Q_run, const float* h0, const float* c0, float* H_out,
+                   float* c_out, void* hip_stream) {
+    if (model == nullptr || X == nullptr || H_out == nullptr) return ELM_EINVAL;
+    if (N < 1 || Q_run < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    ELM_HIP_TRY(launch_hidden(model->lay, model->dWp, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out,
+                              static_cast<hipStream_t>(hip_stream)));
+    return ELM_OK;
+}
+
+size_t elm_rnn_solve_workspace_bytes(int64_t N, int L, int m) {
+    if (N < 1 || L < 1 || m < 1 || L > 512 || m > 16) return 0;
+    return make_solve_plan(N, L, m).bytes;
+}
+
+int elm_rnn_solve(const float* H, const float* T, int64_t N, int L, int m, int refine,
+                  float* beta_out, double* beta64_out, elm_rnn_stats* stats, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+    return run_solve(H, T, N, L, m, refine, beta_out, beta64_out, stats, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream), 0.0, nullptr);
+}
+
+size_t elm_rnn_fit_workspace_bytes(int64_t N, int L, int m, int h_in_workspace) {
+    const size_t s = elm_rnn_solve_workspace_bytes(N, L, m);
+    if (s == 0) return 0;
+    return s + (h_in_workspace ? (((size_t)N * L * sizeof(float) + 255) & ~(size_t)255) : 0);
+}
+
+int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T, int64_t N,
+                int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init, void* workspace,
+                size_t workspace_bytes, void* hip_stream, float* H_out, float* beta_out,
+                double* beta64_out, elm_rnn_stats* stats, elm_rnn_model** model_out) {
+    if (X == nullptr || T == nullptr || beta_out == nullptr || model_out == nullptr) return ELM_EINVAL;
+    if (N < 1 || N < L) return ELM_EINVAL;
+    int rc = check_dims(cell, Q, d, L, m);
+    if (rc != ELM_OK) return rc;
+    const size_t need = elm_rnn_fit_workspace_bytes(N, L, m, H_out == nullptr);
+    if (workspace == nullptr || workspace_bytes < need) return ELM_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    elm_rnn_model* mdl = nullptr;
+    rc = elm_rnn_model_create(cell, Q, d, L, m, seed, init, &mdl);
+    if (rc != ELM_OK) return rc;
+
+    const size_t solve_bytes = elm_rnn_solve_workspace_bytes(N, L, m);
+    float* H = H_out ? H_out : reinterpret_cast<float*>(static_cast<char*>(workspace) + solve_bytes);
+
+    EventPair ev;
+    hipError_t e = ev.create();
+    if (e == hipSuccess) e = hipEventRecord(ev.a, stream);
+    if (e == hipSuccess)
+        e = launch_hidden(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q, nullptr, nullptr, H, nullptr, stream);
+    if (e == hipSuccess) e = hipEventRecord(ev.b, stream);
+    if (e != hipSuccess) {
+        set_hip_error(e, "hidden-matrix stage");
+        elm_rnn_free(mdl);
+        return ELM_EHIP;
+    }
+    // stage 2 is timed from the end of stage 1; the hidden time is read after the final sync
+    elm_rnn_stats local{};
+    rc = run_solve(H, T, N, L, m, 2, beta_out, beta64_out, &local, workspace, solve_bytes, stream, 0.0,
+                   ev.b);
+    if (rc != ELM_OK && rc != ELM_ERANK) {
+        elm_rnn_free(mdl);
+        return rc;
+    }
+    float hms = 0.0f;
+    e = hipEventElapsedTime(&hms, ev.a, ev.b);
+    if (e == hipSuccess) {
+        const double* small = reinterpret_cast<const double*>(static_cast<const char*>(workspace) +
+                                                              make_solve_plan(N, L, m).off_small);
+        e = hipMemcpyAsync(mdl->dBeta, small + SmallArea::BETA, (size_t)L * m * sizeof(double),
+                           hipMemcpyDeviceToDevice, stream);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        set_hip_error(e, "fit epilogue");
+        elm_rnn_free(mdl);
+        return ELM_EHIP;
+    }
+    local.t_hidden_ms = hms;
+    if (stats) *stats = local;
+    *model_out = mdl;
+    return rc;
+}
+
+size_t elm_rnn_predict_workspace_bytes(int64_t N, int L) {
+    if (N < 1 || L < 1) return 0;
+    return ((size_t)N * L * sizeof(float) + 255) & ~(size_t)255;
+}
+
+int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
+                    int64_t N, float* Y_out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+    if (model == nullptr || X == nullptr || Y_out == nullptr || N < 1) return ELM_EINVAL;
+    if (workspace == nullptr || workspace_bytes < elm_rnn_predict_workspace_bytes(N, model->L))
+        return ELM_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float* H = static_cast<float*>(workspace);
+    ELM_HIP_TRY(launch_hidden(model->lay, model->dWp, X, ldx_n, ldx_q, N, model->Q, nullptr, nullptr, H,
+                              nullptr, stream));
+    ELM_HIP_TRY(launch_predict_gemv(H, model->dBeta, N, model->L, model->m, Y_out, stream));
+    return ELM_OK;
+}
+
+const char* elm_rnn_strerror(int code) {
+    switch (code) {
+        case ELM_OK: return "ok";
+        case ELM_EINVAL: return "invalid argument";
+        case ELM_EWORKSPACE: return "workspace missing or too small";
+        case ELM_ERANK: return "hidden matrix is numerically rank deficient";
+        case ELM_EHIP: return "HIP runtime error";
+        case ELM_EUNSUPPORTED: return "size outside the supported range";
+        default: return "unknown error code";
+    }
+}
+
+const char* elm_rnn_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

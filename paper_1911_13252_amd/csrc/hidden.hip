@@ -1,0 +1,422 @@
+// Stage 1: the hidden-matrix build H(Q) (step 2 of the paper's Algorithm "S-R-ELM").
+//
+// One work-group owns a tile of S = 32*MS windows for all Q steps.  Per step it evaluates the
+// gate pre-activations  A_t = [h_{t-1} | x_t | 1] . [U; W; b]  as a dense fp32 MFMA contraction
+// (samples x K) . (K x G*L), then the cell's point-wise update (the paper's sections "Elman",
+// "LSTM", "GRU").  The activation operand [h | x | 1] lives in LDS for the whole unroll, the cell
+// state c (and the freshly computed h until every wave has finished reading the old one) lives
+// in registers, the weights stream from L2 in a pre-packed fragment order.  HBM is read once per
+// window element and written once per H row.
+//
+// Differences from the paper's Opt-PR-ELM kernel (Algorithm "Opt-PR-ELM", one thread per
+// (sample, neuron) with BSxBS shared-memory tiles): the per-step H(t) is never stored, the
+// recurrence is a dense L x L lag-1 matrix, and the tiling is by 64-lane wavefront MFMA tiles.
+
+#include "internal.h"
+
+namespace elm {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;      // 4 wavefronts, one per SIMD
+constexpr int kXPT = 4;            // input values a thread can prefetch per step
+
+struct HiddenArgs {
+    const float* X;
+    int64_t ldx_n, ldx_q;
+    const float* Wp;
+    const float* h0;
+    const float* c0;
+    float* H;
+    float* C;
+    int64_t N;
+    int Q_run, d, L, R, KG, nJB;
+};
+
+__device__ __forceinline__ float sigmoid_f(float x) {
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+}
+__device__ __forceinline__ float tanh_f(float x) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x));
+}
+
+// acc[g][ms] += A(ms) . B(g) over all k-groups.
+//   A fragment of k-group kg, tile ms: lane (r = lane&31, half = lane>>5) holds
+//     Abuf[(ms*32 + r)*R + kg*8 + half*4 + e], e = 0..3      (one ds_read_b128)
+//   B fragment of k-group kg, gate g: lane holds 4 floats at bp[(kg*GT + g)*256 + e]
+//     = weight row kg*8 + half*4 + e, column (lane&31) of that gate's 32-column block.
+//   MFMA step e therefore contracts k-slots {kg*8+e, kg*8+4+e}; every k is covered once.
+template <int G, int GT, int MS, int PF>
+__device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __restrict__ Abuf,
+                                         int R, const float* __restrict__ bp, int KG, int lane) {
+    const float* ap = Abuf + (lane & 31) * R + (lane >> 5) * 4;
+    // PF k-groups of weight fragments are kept in flight; the loads for group kg+PF are issued
+    // before the MFMAs of group kg so that their latency hides behind PF groups of matrix work.
+    floatx4 bq[PF][G];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            bq[u][g] = *reinterpret_cast<const floatx4*>(bp + ((size_t)u * GT + g) * 256);
+
+    for (int kg = 0; kg < KG; kg += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            if (kg + u < KG) {
+                floatx4 b[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) b[g] = bq[u][g];
+                floatx4 a[MS];
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    a[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * R + (kg + u) * 8);
+                // refill this slot with the group PF ahead (the packed buffer has a PF-group tail)
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    bq[u][g] = *reinterpret_cast<const floatx4*>(
+                        bp + ((size_t)(kg + u + PF) * GT + g) * 256);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int ms = 0; ms < MS; ++ms)
+                            acc[g][ms] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ms][e], b[g][e],
+                                                                              acc[g][ms], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
+
+template <int CELL, int MS, int NCH>
+__global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
+    constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
+    constexpr int S = 32 * MS;
+    constexpr int PF = (G >= 3) ? 2 : 4;
+    extern __shared__ __align__(16) float lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int L = p.L, R = p.R, d = p.d, KG = p.KG;
+    const int64_t row0 = (int64_t)blockIdx.x * S;
+    float* A0 = lds;               // [S][R]: h_{t-1} | x_t | 1 | 0...
+    float* A1 = lds + S * R;       // GRU only: (r*h_{t-1}) | x_t | 1 | 0...
+
+    // accumulator element (ms, i) of this lane: sample row, hidden column inside the block
+    const int col_in = lane & 31;
+    auto acc_row = [&](int ms, int i) { return ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
+
+    // ---- initial contents of the activation operand
+    for (int idx = tid; idx < S * R; idx += kThreads) {
+        const int s = idx / R, k = idx - s * R;
+        const int64_t row = row0 + s;
+        float v = 0.0f;
+        if (k < L) {
+            if (p.h0 != nullptr && row < p.N) v = p.h0[row * L + k];
+        } else if (k == L + d) {
+            v = 1.0f;
+        }
+        A0[idx] = v;
+        if (CELL == ELM_CELL_GRU) A1[idx] = (k == L + d) ? 1.0f : 0.0f;
+    }
+
+    const int nx = S * d;                          // input values per step for this tile
+    const bool x_prefetch = nx <= kThreads * kXPT;
+    float xr[kXPT];
+    auto load_x = [&](int t) {
+#pragma unroll
+        for (int q = 0; q < kXPT; ++q) {
+            const int e = tid + q * kThreads;
+            xr[q] = 0.0f;
+            if (e < nx) {
+                const int s = e / d, dd = e - s * d;
+                const int64_t row = row0 + s;
+                if (row < p.N) xr[q] = p.X[row * p.ldx_n + (int64_t)t * p.ldx_q + dd];
+            }
+        }
+    };
+    auto store_x = [&](float* buf) {
+#pragma unroll
+        for (int q = 0; q < kXPT; ++q) {
+            const int e = tid + q * kThreads;
+            if (e < nx) {
+                const int s = e / d, dd = e - s * d;
+                buf[s * R + L + dd] = xr[q];
+            }
+        }
+    };
+    auto copy_x_direct = [&](int t, float* buf) {     // wide inputs: no register staging
+        for (int e = tid; e < nx; e += kThreads) {
+            const int s = e / d, dd = e - s * d;
+            const int64_t row = row0 + s;
+            buf[s * R + L + dd] =
+                (row < p.N) ? p.X[row * p.ldx_n + (int64_t)t * p.ldx_q + dd] : 0.0f;
+        }
+    };
+
+    // ---- register-resident state
+    float st[NCH][MS][16];     // LSTM: cell state c; GRU: this lane's own copy of h; Elman: unused
+    float hn[NCH][MS][16];     // LSTM/Elman: new h until the old one is dead; GRU: update gate z
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int jb = ch * 4 + wave;
+        const int col = jb * 32 + col_in;
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = 0.0f;
+                const int64_t row = row0 + acc_row(ms, i);
+                const float* src = (CELL == ELM_CELL_LSTM) ? p.c0 : (CELL == ELM_CELL_GRU) ? p.h0 : nullptr;
+                if (src != nullptr && row < p.N && col < L) v = src[row * L + col];
+                st[ch][ms][i] = v;
+                hn[ch][ms][i] = 0.0f;
+            }
+    }
+    __syncthreads();       // A0/A1 constants written before the x slots are filled
+    if (x_prefetch) {
+        load_x(0);
+        store_x(A0);
+        // the GRU's second operand gets x_0 at the top of the first step
+    } else {
+        copy_x_direct(0, A0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < p.Q_run; ++t) {
+        if (CELL == ELM_CELL_GRU) {
+            if (x_prefetch) store_x(A1); else copy_x_direct(t, A1);
+        }
+        const bool more = (t + 1 < p.Q_run);
+        if (x_prefetch && more) load_x(t + 1);
+
+        if (CELL != ELM_CELL_GRU) {
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int jb = ch * 4 + wave;
+                if (jb < p.nJB) {
+                    floatx16 acc[G][MS];
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
+                    const float* bp = p.Wp + (size_t)jb * KG * G * 256 + lane * 4;
+                    contract<G, G, MS, PF>(acc, A0, R, bp, KG, lane);
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            if (CELL == ELM_CELL_ELMAN) {
+                                hn[ch][ms][i] = tanh_f(acc[0][ms][i]);
+                            } else {
+                                const float ig = sigmoid_f(acc[0][ms][i]);
+                                const float fg = sigmoid_f(acc[G > 1 ? 1 : 0][ms][i]);
+                                const float og = sigmoid_f(acc[G > 2 ? 2 : 0][ms][i]);
+                                const float gg = tanh_f(acc[G > 3 ? 3 : 0][ms][i]);
+                                const float c = fg * st[ch][ms][i] + ig * gg;
+                                st[ch][ms][i] = c;
+                                hn[ch][ms][i] = og * tanh_f(c);
+                            }
+                        }
+                }
+            }
+            __syncthreads();          // every wave has finished reading h_{t-1}
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int jb = ch * 4 + wave;
+                const int col = jb * 32 + col_in;
+                if (jb < p.nJB && col < L) {
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) A0[acc_row(ms, i) * R + col] = hn[ch][ms][i];
+                }
+            }
+            if (more) {
+                if (x_prefetch) store_x(A0); else copy_x_direct(t + 1, A0);
+            }
+            __syncthreads();
+        } else {
+            // phase 1: update and reset gates from h_{t-1}; stage r*h_{t-1} as the second operand
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int jb = ch * 4 + wave;
+                const int col = jb * 32 + col_in;
+                if (jb < p.nJB) {
+                    floatx16 acc[2][MS];
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
+                    const float* bp = p.Wp + (size_t)jb * KG * 3 * 256 + lane * 4;
+                    contract<2, 3, MS, 4>(acc, A0, R, bp, KG, lane);
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            hn[ch][ms][i] = sigmoid_f(acc[0][ms][i]);
+                            const float r = sigmoid_f(acc[1][ms][i]);
+                            if (col < L) A1[acc_row(ms, i) * R + col] = r * st[ch][ms][i];
+                        }
+                }
+            }
+            __syncthreads();
+            // phase 2: candidate from r*h_{t-1}; blend; publish h_t into the first operand
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const int jb = ch * 4 + wave;
+                const int col = jb * 32 + col_in;
+                if (jb < p.nJB) {
+                    floatx16 acc[1][MS];
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[0][ms][i] = 0.0f;
+                    const float* bp = p.Wp + ((size_t)jb * KG * 3 + 2) * 256 + lane * 4;
+                    contract<1, 3, MS, 4>(acc, A1, R, bp, KG, lane);
+#pragma unroll
+                    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float z = hn[ch][ms][i];
+                            const float hv = (1.0f - z) * st[ch][ms][i] + z * tanh_f(acc[0][ms][i]);
+                            st[ch][ms][i] = hv;
+                            if (col < L) A0[acc_row(ms, i) * R + col] = hv;
+                        }
+                }
+            }
+            if (more) {
+                if (x_prefetch) store_x(A0); else copy_x_direct(t + 1, A0);
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- H(Q): the h part of the operand, written row by row (coalesced)
+    for (int idx = tid; idx < S * L; idx += kThreads) {
+        const int s = idx / L, j = idx - s * L;
+        const int64_t row = row0 + s;
+        if (row < p.N) p.H[row * L + j] = A0[s * R + j];
+    }
+    if (CELL == ELM_CELL_LSTM && p.C != nullptr) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int jb = ch * 4 + wave;
+            const int col = jb * 32 + col_in;
+            if (jb < p.nJB && col < L) {
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int64_t row = row0 + acc_row(ms, i);
+                        if (row < p.N) p.C[row * L + col] = st[ch][ms][i];
+                    }
+            }
+        }
+    }
+}
+
+template <int CELL, int MS, int NCH>
+hipError_t launch_variant(const HiddenArgs& a, int64_t tiles, size_t lds_bytes, hipStream_t stream) {
+    auto kern = hidden_kernel<CELL, MS, NCH>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+template <int CELL, int MS>
+hipError_t launch_nch(int nch, const HiddenArgs& a, int64_t tiles, size_t lds, hipStream_t s) {
+    switch (nch) {
+        case 1: return launch_variant<CELL, MS, 1>(a, tiles, lds, s);
+        case 2: return launch_variant<CELL, MS, 2>(a, tiles, lds, s);
+        case 3: return launch_variant<CELL, MS, 3>(a, tiles, lds, s);
+        case 4: return launch_variant<CELL, MS, 4>(a, tiles, lds, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int CELL>
+hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t lds_per_row,
+                       hipStream_t s) {
+    const int S = 32 * ms;
+    const int64_t tiles = (N + S - 1) / S;
+    const size_t lds = lds_per_row * S;
+    if (ms == 2) return launch_nch<CELL, 2>(nch, a, tiles, lds, s);
+    return launch_nch<CELL, 1>(nch, a, tiles, lds, s);
+}
+
+}  // namespace
+
+PackedLayout packed_layout(int cell, int d, int L) {
+    PackedLayout lay{};
+    lay.cell = cell;
+    lay.d = d;
+    lay.L = L;
+    lay.G = gates_of(cell);
+    lay.K = L + d + 1;
+    lay.KG = (lay.K + 7) / 8;
+    lay.R = 8 * lay.KG + 4;
+    lay.nJB = (L + 31) / 32;
+    // 4 extra k-groups: the contraction's look-ahead loads read (harmlessly) past the last group
+    lay.floats = ((size_t)lay.nJB * lay.KG + 4) * lay.G * 256;
+    return lay;
+}
+
+void pack_weights(const PackedLayout& lay, const float* W, const float* U, const float* b, float* out) {
+    const int L = lay.L, d = lay.d, G = lay.G, GL = G * L;
+    for (size_t i = 0; i < lay.floats; ++i) out[i] = 0.0f;
+    for (int jb = 0; jb < lay.nJB; ++jb)
+        for (int kg = 0; kg < lay.KG; ++kg)
+            for (int g = 0; g < G; ++g)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 4; ++e) {
+                        const int k = kg * 8 + (lane >> 5) * 4 + e;
+                        const int j = jb * 32 + (lane & 31);
+                        if (k >= lay.K || j >= L) continue;
+                        const int col = g * L + j;
+                        float v;
+                        if (k < L) v = U[(size_t)k * GL + col];
+                        else if (k < L + d) v = W[(size_t)(k - L) * GL + col];
+                        else v = b[col];
+                        out[((((size_t)jb * lay.KG + kg) * G + g) * 64 + lane) * 4 + e] = v;
+                    }
+}
+
+hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
+                         int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
+                         float* H, float* C, hipStream_t stream) {
+    int dev = 0, lds_max = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return e;
+
+    const int nbuf = (lay.cell == ELM_CELL_GRU) ? 2 : 1;
+    const size_t lds_per_row = (size_t)nbuf * lay.R * sizeof(float);
+    int ms = 2;
+    if (lds_per_row * 64 > (size_t)lds_max) ms = 1;
+    if (lds_per_row * 32 > (size_t)lds_max) return hipErrorInvalidValue;
+    const int nch = (lay.nJB + 3) / 4;
+
+    HiddenArgs a{};
+    a.X = X; a.ldx_n = ldx_n; a.ldx_q = ldx_q; a.Wp = Wp; a.h0 = h0; a.c0 = c0;
+    a.H = H; a.C = C; a.N = N; a.Q_run = Q_run; a.d = lay.d; a.L = lay.L; a.R = lay.R;
+    a.KG = lay.KG; a.nJB = lay.nJB;
+    switch (lay.cell) {
+        case ELM_CELL_ELMAN: return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, stream);
+        case ELM_CELL_LSTM:  return launch_cell<ELM_CELL_LSTM>(ms, nch, a, N, lds_per_row, stream);
+        case ELM_CELL_GRU:   return launch_cell<ELM_CELL_GRU>(ms, nch, a, N, lds_per_row, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace elm

@@ -1,0 +1,77 @@
+// Internal declarations shared by the translation units of libelmrnn (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "elm_rnn.h"
+
+namespace elm {
+
+// Geometry of the packed weight operand [U; W; b] (K x G*L) as the hidden-matrix kernel reads it.
+struct PackedLayout {
+    int cell, d, L, G;
+    int K;        // L + d + 1 contraction rows: recurrent, input, bias
+    int KG;       // k-groups of 8 rows (ceil(K / 8))
+    int R;        // LDS row stride of the activation operand, 8*KG + 4 floats
+    int nJB;      // hidden-unit blocks of 32 columns (ceil(L / 32))
+    size_t floats;   // packed buffer length including the prefetch tail
+};
+
+inline int gates_of(int cell) { return cell == ELM_CELL_ELMAN ? 1 : cell == ELM_CELL_LSTM ? 4 : 3; }
+PackedLayout packed_layout(int cell, int d, int L);
+
+// Pack host W (d x GL), U (L x GL), b (GL) into the kernel's fragment order.
+void pack_weights(const PackedLayout& lay, const float* W, const float* U, const float* b, float* out);
+
+hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
+                         int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
+                         float* H, float* C, hipStream_t stream);
+
+// ---- stage 2 -------------------------------------------------------------------------------
+struct SolvePlan {
+    int64_t N;
+    int L, m, n, np;       // n = L + m columns, np = n rounded up to 32
+    int levels;            // number of fold launches (level 0 + combine levels)
+    int groups[8];         // work-groups (= R factors produced) per level
+    size_t off_R[2];       // ping-pong R-factor stacks (bytes from workspace base)
+    size_t off_part;       // per-work-group partial sums of the residual pass (doubles)
+    size_t off_small;      // beta64, gradient, scalars (doubles)
+    size_t bytes;
+};
+SolvePlan make_solve_plan(int64_t N, int L, int m);
+
+hipError_t launch_tsqr(const SolvePlan& plan, const float* H, const float* T, void* ws,
+                       float** R_final, hipStream_t stream);
+hipError_t launch_backsolve(const SolvePlan& plan, const float* R, void* ws, hipStream_t stream);
+hipError_t launch_residual_pass(const SolvePlan& plan, const float* H, const float* T, void* ws,
+                                hipStream_t stream);
+hipError_t launch_refine_update(const SolvePlan& plan, const float* R, void* ws, hipStream_t stream);
+hipError_t launch_export_beta(const SolvePlan& plan, void* ws, float* beta32, double* beta64,
+                              hipStream_t stream);
+hipError_t launch_predict_gemv(const float* H, const double* beta64, int64_t N, int L, int m,
+                               float* Y, hipStream_t stream);
+
+// layout of the "small" double area of the solve workspace
+struct SmallArea {
+    static constexpr int BETA = 0;                 // L*m      current beta (float64)
+    __host__ __device__ static size_t grad(int L, int m) { return (size_t)L * m; }            // L*m   H^T r
+    __host__ __device__ static size_t scal(int L, int m) { return (size_t)2 * L * m; }        // 8 scalars:
+    // [0] rss  [1] sum H^2  [2] ||g||^2  [3] rss from R22  [4] min|Rjj|  [5] max|Rjj|  [6] rank flag
+    __host__ __device__ static size_t doubles(int L, int m) { return (size_t)2 * L * m + 8; }
+};
+
+void set_hip_error(hipError_t e, const char* where);
+
+}  // namespace elm
+
+#define ELM_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) {                            \
+            elm::set_hip_error(e__, #expr);                 \
+            return ELM_EHIP;                                \
+        }                                                   \
+    } while (0)

@@ -1,0 +1,387 @@
+// Stage 2b: from the R factor of [H | T] to beta (the paper's section "Computing beta":
+// "beta would be the solution of R beta = z by back substitution"), plus float64-residual
+// iterative refinement of beta and the prediction product Y = H beta (the paper's output equation
+// y_hat = sum_i beta_i f_i).
+//
+// R = [R11 R12; 0 R22] (np x np float32, upper triangular).  beta0 = R11^{-1} R12 in float64
+// arithmetic.  A refinement step streams H once:  r = T - H beta and g = H^T r accumulated in
+// float64, then  beta += (R11^T R11)^{-1} g  by one forward and one backward triangular solve.
+
+#include "internal.h"
+
+namespace elm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileRows = 32;
+
+// ---- triangular solves on one work-group: blocks of 32, diagonal block by one wave in registers
+// y (LDS, doubles, length >= 32*ceil(L/32)) is overwritten by the solution of R11 x = y.
+__device__ void solve_upper(const float* __restrict__ R, int np, int L, double* y) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nb = (L + 31) / 32;
+    for (int kb = nb - 1; kb >= 0; --kb) {
+        const int c0 = kb * 32;
+        if (tid < 64) {
+            const int i = lane & 31, row = c0 + i;
+            double drow[32];
+#pragma unroll
+            for (int l = 0; l < 32; ++l) {
+                const int col = c0 + l;
+                double v = (l == i) ? 1.0 : 0.0;
+                if (row < L && col < L) v = (double)R[(size_t)row * np + col];
+                drow[l] = v;
+            }
+            double yi = (row < L) ? y[row] : 0.0;
+#pragma unroll
+            for (int k = 31; k >= 0; --k) {
+                const double xk = __shfl(yi, k) / __shfl(drow[k], k);
+                if (i == k) yi = xk;
+                else if (i < k) yi -= drow[k] * xk;
+            }
+            if (lane < 32 && row < L) y[row] = yi;
+        }
+        __syncthreads();
+        for (int i = tid; i < c0; i += kThreads) {
+            double acc = 0.0;
+            const float* rr = R + (size_t)i * np + c0;
+            for (int l = 0; l < 32; ++l)
+                if (c0 + l < L) acc += (double)rr[l] * y[c0 + l];
+            y[i] -= acc;
+        }
+        __syncthreads();
+    }
+}
+
+// y is overwritten by the solution of R11^T x = y.
+__device__ void solve_upper_transposed(const float* __restrict__ R, int np, int L, double* y) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nb = (L + 31) / 32;
+    for (int kb = 0; kb < nb; ++kb) {
+        const int c0 = kb * 32;
+        if (tid < 64) {
+            const int i = lane & 31, col = c0 + i;
+            double dcol[32];      // dcol[l] = R[c0+l][c0+i]
+#pragma unroll
+            for (int l = 0; l < 32; ++l) {
+                const int row = c0 + l;
+                double v = (l == i) ? 1.0 : 0.0;
+                if (row < L && col < L) v = (double)R[(size_t)row * np + col];
+                dcol[l] = v;
+            }
+            double yi = (col < L) ? y[col] : 0.0;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) {
+                const double xk = __shfl(yi, k) / __shfl(dcol[k], k);
+                if (i == k) yi = xk;
+                else if (i > k) yi -= dcol[k] * xk;
+            }
+            if (lane < 32 && col < L) y[col] = yi;
+        }
+        __syncthreads();
+        for (int jj = c0 + 32 + tid; jj < L; jj += kThreads) {
+            double acc = 0.0;
+            for (int l = 0; l < 32; ++l)
+                if (c0 + l < L) acc += (double)R[(size_t)(c0 + l) * np + jj] * y[c0 + l];
+            y[jj] -= acc;
+        }
+        __syncthreads();
+    }
+}
+
+// beta0 = R11^{-1} R12, diagnostics of R.
+__global__ __launch_bounds__(kThreads) void backsolve_kernel(const float* __restrict__ R, int np, int L,
+                                                             int m, double* small) {
+    __shared__ double y[544];
+    __shared__ double sred[kThreads];
+    __shared__ double smin[kThreads], smax[kThreads];
+    const int tid = threadIdx.x;
+    double* beta = small + SmallArea::BETA;
+    double* scal = small + SmallArea::scal(L, m);
+
+    // residual mass left in the T columns below row L, and the diagonal range of R11
+    double rs = 0.0, dmin = 1e300, dmax = 0.0;
+    for (int idx = tid; idx < m * m; idx += kThreads) {
+        const int i = idx / m, jx = idx - i * m;
+        if (jx >= i) {
+            const double v = (double)R[(size_t)(L + i) * np + L + jx];
+            rs += v * v;
+        }
+    }
+    for (int k = tid; k < L; k += kThreads) {
+        const double v = fabs((double)R[(size_t)k * np + k]);
+        dmin = fmin(dmin, v);
+        dmax = fmax(dmax, v);
+    }
+    sred[tid] = rs; smin[tid] = dmin; smax[tid] = dmax;
+    __syncthreads();
+    for (int s = kThreads / 2; s > 0; s >>= 1) {
+        if (tid < s) {
+            sred[tid] += sred[tid + s];
+            smin[tid] = fmin(smin[tid], smin[tid + s]);
+            smax[tid] = fmax(smax[tid], smax[tid + s]);
+        }
+        __syncthreads();
+    }
+    const bool deficient = !(smin[0] > 1.1920928955078125e-07 * smax[0]);
+    if (tid == 0) {
+        scal[3] = sred[0];
+        scal[4] = smin[0];
+        scal[5] = smax[0];
+        scal[6] = deficient ? 1.0 : 0.0;
+    }
+    for (int c = 0; c < m; ++c) {
+        for (int i = tid; i < 544; i += kThreads) y[i] = (i < L) ? (double)R[(size_t)i * np + L + c] : 0.0;
+        __syncthreads();
+        if (!deficient) solve_upper(R, np, L, y);
+        for (int i = tid; i < L; i += kThreads) beta[(size_t)i * m + c] = deficient ? 0.0 : y[i];
+        __syncthreads();
+    }
+}
+
+// beta += (R11^T R11)^{-1} g
+__global__ __launch_bounds__(kThreads) void refine_kernel(const float* __restrict__ R, int np, int L,
+                                                          int m, double* small) {
+    __shared__ double y[544];
+    const int tid = threadIdx.x;
+    double* beta = small + SmallArea::BETA;
+    const double* grad = small + SmallArea::grad(L, m);
+    const double* scal = small + SmallArea::scal(L, m);
+    if (scal[6] != 0.0) return;       // rank deficient: leave beta alone
+    for (int c = 0; c < m; ++c) {
+        for (int i = tid; i < 544; i += kThreads) y[i] = (i < L) ? grad[(size_t)i * m + c] : 0.0;
+        __syncthreads();
+        solve_upper_transposed(R, np, L, y);
+        solve_upper(R, np, L, y);
+        for (int i = tid; i < L; i += kThreads) beta[(size_t)i * m + c] += y[i];
+        __syncthreads();
+    }
+}
+
+// One streaming pass over H.  MODE 0: per-work-group partial sums of g = H^T (T - H beta),
+// ||T - H beta||^2 and ||H||^2.  MODE 1: Y = H beta.
+template <int M, int MODE>
+__global__ __launch_bounds__(kThreads) void stream_kernel(const float* __restrict__ H,
+                                                          const float* __restrict__ T, int64_t N, int L,
+                                                          int m, const double* __restrict__ beta,
+                                                          double* __restrict__ part, float* __restrict__ Y) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int ldh = L + 1;
+    double* bs = reinterpret_cast<double*>(smem);                        // [L][M]
+    double* rs = bs + (size_t)L * M;                                     // [32][M]
+    float* Hs = reinterpret_cast<float*>(rs + kTileRows * M);            // [32][ldh]
+    __shared__ double sred[kThreads];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < L * M; idx += kThreads) {
+        const int jx = idx / M, c = idx - jx * M;
+        bs[idx] = (c < m) ? beta[(size_t)jx * m + c] : 0.0;
+    }
+    double gacc[2][M];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int c = 0; c < M; ++c) gacc[q][c] = 0.0;
+    double rss = 0.0, h2 = 0.0;
+
+    const int64_t ntiles = (N + kTileRows - 1) / kTileRows;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t r0 = tile * kTileRows;
+        __syncthreads();                       // previous tile fully consumed (and bs written)
+        for (int idx = tid; idx < kTileRows * L; idx += kThreads) {
+            const int r = idx / L, c = idx - r * L;
+            const int64_t row = r0 + r;
+            const float v = (row < N) ? H[row * L + c] : 0.0f;
+            Hs[r * ldh + c] = v;
+            if (MODE == 0) h2 += (double)v * (double)v;
+        }
+        __syncthreads();
+        {   // 8 lanes per row: partial dot products, then a shuffle reduction over the 8
+            const int r = tid >> 3, sub = tid & 7;
+            double acc[M];
+#pragma unroll
+            for (int c = 0; c < M; ++c) acc[c] = 0.0;
+            for (int jx = sub; jx < L; jx += 8) {
+                const double hv = (double)Hs[r * ldh + jx];
+#pragma unroll
+                for (int c = 0; c < M; ++c) acc[c] = fma(hv, bs[jx * M + c], acc[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < M; ++c) {
+                acc[c] += __shfl_xor(acc[c], 1);
+                acc[c] += __shfl_xor(acc[c], 2);
+                acc[c] += __shfl_xor(acc[c], 4);
+            }
+            const int64_t row = r0 + r;
+            if (sub == 0) {
+#pragma unroll
+                for (int c = 0; c < M; ++c) {
+                    if (MODE == 0) {
+                        double res = 0.0;
+                        if (row < N && c < m) res = (double)T[row * m + c] - acc[c];
+                        rs[r * M + c] = res;
+                        rss += res * res;
+                    } else if (row < N && c < m) {
+                        Y[row * m + c] = (float)acc[c];
+                    }
+                }
+            }
+        }
+        if (MODE == 0) {
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int jx = tid + q * kThreads;
+                if (jx < L) {
+                    for (int r = 0; r < kTileRows; ++r) {
+                        const double hv = (double)Hs[r * ldh + jx];
+#pragma unroll
+                        for (int c = 0; c < M; ++c) gacc[q][c] = fma(hv, rs[r * M + c], gacc[q][c]);
+                    }
+                }
+            }
+        }
+    }
+    if (MODE == 0) {
+        double* mypart = part + (size_t)blockIdx.x * ((size_t)L * m + 2);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int jx = tid + q * kThreads;
+            if (jx < L)
+#pragma unroll
+                for (int c = 0; c < M; ++c)
+                    if (c < m) mypart[(size_t)jx * m + c] = gacc[q][c];
+        }
+        __syncthreads();
+        sred[tid] = rss;
+        __syncthreads();
+        for (int s = kThreads / 2; s > 0; s >>= 1) {
+            if (tid < s) sred[tid] += sred[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0) mypart[(size_t)L * m] = sred[0];
+        __syncthreads();
+        sred[tid] = h2;
+        __syncthreads();
+        for (int s = kThreads / 2; s > 0; s >>= 1) {
+            if (tid < s) sred[tid] += sred[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0) mypart[(size_t)L * m + 1] = sred[0];
+    }
+}
+
+// Sum the per-work-group partials in a fixed order; scal[0..2] = rss, sum H^2, ||g||^2.
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part,
+                                                                   int nparts, int L, int m,
+                                                                   double* small) {
+    __shared__ double sred[kThreads];
+    const int tid = threadIdx.x;
+    const int nout = L * m + 2;
+    double* grad = small + SmallArea::grad(L, m);
+    double* scal = small + SmallArea::scal(L, m);
+    double g2 = 0.0;
+    for (int o = tid; o < nout; o += kThreads) {
+        double s = 0.0;
+        for (int w = 0; w < nparts; ++w) s += part[(size_t)w * nout + o];
+        if (o < L * m) {
+            grad[o] = s;
+            g2 += s * s;
+        } else {
+            scal[o - L * m] = s;
+        }
+    }
+    sred[tid] = g2;
+    __syncthreads();
+    for (int s = kThreads / 2; s > 0; s >>= 1) {
+        if (tid < s) sred[tid] += sred[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) scal[2] = sred[0];
+}
+
+__global__ void export_beta_kernel(const double* __restrict__ beta, int count, float* b32, double* b64) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) {
+        b32[i] = (float)beta[i];
+        if (b64 != nullptr) b64[i] = beta[i];
+    }
+}
+
+size_t stream_lds_bytes(int L, int M) {
+    return ((size_t)L * M + kTileRows * M) * sizeof(double) + (size_t)kTileRows * (L + 1) * sizeof(float);
+}
+
+int stream_grid(int64_t N) {
+    const int64_t ntiles = (N + kTileRows - 1) / kTileRows;
+    return (int)(ntiles < 1024 ? ntiles : 1024);
+}
+
+template <int MODE>
+hipError_t launch_stream(const float* H, const float* T, int64_t N, int L, int m, const double* beta,
+                         double* part, float* Y, hipStream_t stream) {
+    const int grid = stream_grid(N);
+    int M = 1;
+    while (M < m) M *= 2;
+    const size_t lds = stream_lds_bytes(L, M);
+#define ELM_STREAM_CASE(MM)                                                                         \
+    case MM: {                                                                                      \
+        auto kern = stream_kernel<MM, MODE>;                                                        \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
+        if (e != hipSuccess) return e;                                                              \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, H, T, N, L, m, beta, part, Y); \
+        return hipGetLastError();                                                                   \
+    }
+    switch (M) {
+        ELM_STREAM_CASE(1)
+        ELM_STREAM_CASE(2)
+        ELM_STREAM_CASE(4)
+        ELM_STREAM_CASE(8)
+        ELM_STREAM_CASE(16)
+        default: return hipErrorInvalidValue;
+    }
+#undef ELM_STREAM_CASE
+}
+
+}  // namespace
+
+hipError_t launch_backsolve(const SolvePlan& pl, const float* R, void* ws, hipStream_t stream) {
+    double* small = reinterpret_cast<double*>(static_cast<char*>(ws) + pl.off_small);
+    hipLaunchKernelGGL(backsolve_kernel, dim3(1), dim3(kThreads), 0, stream, R, pl.np, pl.L, pl.m, small);
+    return hipGetLastError();
+}
+
+hipError_t launch_residual_pass(const SolvePlan& pl, const float* H, const float* T, void* ws,
+                                hipStream_t stream) {
+    char* base = static_cast<char*>(ws);
+    double* small = reinterpret_cast<double*>(base + pl.off_small);
+    double* part = reinterpret_cast<double*>(base + pl.off_part);
+    hipError_t e = launch_stream<0>(H, T, pl.N, pl.L, pl.m, small + SmallArea::BETA, part, nullptr, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kThreads), 0, stream, part,
+                       stream_grid(pl.N), pl.L, pl.m, small);
+    return hipGetLastError();
+}
+
+hipError_t launch_refine_update(const SolvePlan& pl, const float* R, void* ws, hipStream_t stream) {
+    double* small = reinterpret_cast<double*>(static_cast<char*>(ws) + pl.off_small);
+    hipLaunchKernelGGL(refine_kernel, dim3(1), dim3(kThreads), 0, stream, R, pl.np, pl.L, pl.m, small);
+    return hipGetLastError();
+}
+
+hipError_t launch_export_beta(const SolvePlan& pl, void* ws, float* beta32, double* beta64,
+                              hipStream_t stream) {
+    const double* small = reinterpret_cast<const double*>(static_cast<char*>(ws) + pl.off_small);
+    const int count = pl.L * pl.m;
+    hipLaunchKernelGGL(export_beta_kernel, dim3((count + 255) / 256), dim3(256), 0, stream,
+                       small + SmallArea::BETA, count, beta32, beta64);
+    return hipGetLastError();
+}
+
+hipError_t launch_predict_gemv(const float* H, const double* beta64, int64_t N, int L, int m, float* Y,
+                               hipStream_t stream) {
+    return launch_stream<1>(H, nullptr, N, L, m, beta64, nullptr, Y, stream);
+}
+
+}  // namespace elm

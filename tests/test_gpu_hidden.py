@@ -1,0 +1,200 @@
+"""GPU parity: the HIP hidden-matrix kernels against the float64 oracle, element by element.
+
+Tolerance (stated by the benchmark as "H elementwise within 1e-5 relative"; pure relative error
+is unbounded where H crosses zero, so the reference magnitude is floored at the matrix rms):
+    |H_gpu - H_ref| <= 1e-5 * max(|H_ref|, rms(H_ref)).
+Exact-trajectory parity is required wherever the recurrence does not amplify float32 rounding
+beyond that (short horizons, contractive Elman configurations at full Q).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synthdata
+from oracle import cells as ocells
+from oracle import weights as oweights
+
+pytestmark = pytest.mark.gpu
+
+GATES = {"elman": 1, "lstm": 4, "gru": 3}
+
+
+def assert_h_close(got, ref, tol=1e-5):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape
+    rms = np.sqrt(np.mean(ref ** 2)) if ref.size else 0.0
+    bound = tol * np.maximum(np.abs(ref), max(rms, 1e-30))
+    err = np.abs(got - ref)
+    bad = err > bound
+    assert not bad.any(), (f"{bad.sum()} of {bad.size} entries off; max abs err {err.max():.3e}, "
+                           f"worst ratio {np.max(err / bound):.2f}, rms(ref) {rms:.3e}")
+
+
+def rand_weights(cell, d, L, seed, scale=None):
+    k = GATES[cell]
+    rng = np.random.default_rng(seed)
+    a = scale if scale is not None else 1.0 / np.sqrt(L + d)
+    W = rng.uniform(-a, a, (d, k * L)).astype(np.float32)
+    U = rng.uniform(-a, a, (L, k * L)).astype(np.float32)
+    b = rng.uniform(-0.5, 0.5, k * L).astype(np.float32)
+    return W, U, b
+
+
+SHAPES = [  # N, Q, d, L  (several tiles, ragged tails, every chunk count, awkward sizes)
+    (1, 1, 1, 1), (63, 2, 3, 5), (65, 3, 2, 33), (200, 4, 1, 100), (130, 3, 4, 128),
+    (77, 3, 8, 160), (129, 2, 4, 256), (70, 2, 5, 300), (64, 3, 8, 512), (33, 2, 2, 385),
+]
+
+
+@pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
+@pytest.mark.parametrize("N,Q,d,L", SHAPES)
+def test_hidden_matches_oracle_small(elm, cell, N, Q, d, L):
+    W, U, b = rand_weights(cell, d, L, seed=N + 7 * L)
+    X = np.random.default_rng(N + L + Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    ref = ocells.hidden(cell, X, W, U, b)
+    assert_h_close(H, ref)
+    model.close()
+
+
+@pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
+def test_initial_state_truncation_and_cell_output(elm, cell):
+    N, Q, d, L = 150, 6, 3, 70
+    W, U, b = rand_weights(cell, d, L, seed=5)
+    rng = np.random.default_rng(6)
+    X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    h0 = rng.uniform(-0.9, 0.9, (N, L)).astype(np.float32)
+    c0 = rng.uniform(-2, 2, (N, L)).astype(np.float32)
+    model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    Xd, h0d, c0d = (torch.from_numpy(a).cuda() for a in (X, h0, c0))
+    kw = dict(h0=h0d, c0=c0d) if cell == "lstm" else dict(h0=h0d)
+    c_out = torch.empty((N, L), dtype=torch.float32, device="cuda") if cell == "lstm" else None
+    H = elm.hidden(model, Xd, Q_run=4, c_out=c_out, **kw).cpu().numpy()
+    if cell == "lstm":
+        ref, cref = ocells.hidden_lstm(X, W, U, b, h0=h0, c0=c0, steps=4, return_cell=True)
+        assert_h_close(c_out.cpu().numpy(), cref)
+    else:
+        ref = ocells.hidden(cell, X, W, U, b, h0=h0, steps=4)
+    assert_h_close(H, ref)
+    # zero-step-equivalent sanity: one step from a given state equals the oracle's one step
+    H1 = elm.hidden(model, Xd, Q_run=1, **kw).cpu().numpy()
+    ref1 = ocells.hidden(cell, X, W, U, b, h0=h0, steps=1, **({"c0": c0} if cell == "lstm" else {}))
+    assert_h_close(H1, ref1)
+    model.close()
+
+
+def test_zero_copy_sliding_windows_and_wide_inputs(elm):
+    # strided X over a series (ldx_n = d), and d large enough to bypass the register prefetch
+    rng = np.random.default_rng(11)
+    for cell, d, L, Q, N in (("lstm", 4, 40, 5, 300), ("gru", 40, 24, 3, 90), ("elman", 64, 16, 2, 70)):
+        series = rng.uniform(-1, 1, (N + Q, d)).astype(np.float32)
+        W, U, b = rand_weights(cell, d, L, seed=d)
+        sd = torch.from_numpy(series).cuda()
+        Xv = torch.as_strided(sd, (N, Q, d), (d, d, 1))
+        model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+        H = elm.hidden(model, Xv).cpu().numpy()
+        Xh = np.lib.stride_tricks.sliding_window_view(series, (Q, d))[:N, 0]
+        assert_h_close(H, ocells.hidden(cell, Xh, W, U, b))
+        model.close()
+
+
+def test_rows_are_independent_of_tiling(elm):
+    # the same window gives the same row wherever it sits in the batch (bitwise)
+    cell, N, Q, d, L = "lstm", 200, 4, 3, 96
+    W, U, b = rand_weights(cell, d, L, seed=3)
+    X = np.random.default_rng(4).uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    perm = np.random.default_rng(5).permutation(N)
+    Hp = elm.hidden(model, torch.from_numpy(X[perm].copy()).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(Hp, H[perm])
+    H2 = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(H2, H)          # deterministic
+    model.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_seeded_weights_match_the_oracle_generator(elm, name):
+    cfg = synthdata.get_config(name)
+    model = elm.Model.create(cfg.cell, cfg.Q, cfg.d, cfg.L, cfg.m, cfg.seed, w_scale=cfg.w_scale,
+                             spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
+                             zero_bias=cfg.zero_bias)
+    W, U, b, _ = model.weights()
+    Wo, Uo, bo = oweights.draw(cfg.cell, cfg.d, cfg.L, cfg.seed, cfg.w_scale, cfg.spectral_radius,
+                               cfg.forget_bias, cfg.zero_bias)
+    np.testing.assert_array_equal(W, Wo)
+    np.testing.assert_array_equal(b, bo)
+    if cfg.spectral_radius > 0:
+        # two independent spectral-radius algorithms agree to ~1e-14; after float32 rounding a
+        # handful of entries may differ by one unit in the last place
+        assert np.max(np.abs(U.astype(np.float64) - Uo) / np.maximum(np.abs(Uo), 1e-30)) < 2e-7
+        assert np.mean(U != Uo) < 1e-3
+    else:
+        np.testing.assert_array_equal(U, Uo)
+    model.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_contractive_configs_full_horizon(elm, name):
+    cfg = synthdata.get_config(name)
+    _, X, _ = synthdata.make_problem(cfg)
+    model = elm.Model.create(cfg.cell, cfg.Q, cfg.d, cfg.L, cfg.m, cfg.seed, w_scale=cfg.w_scale,
+                             spectral_radius=cfg.spectral_radius)
+    W, U, b, _ = model.weights()
+    H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    assert_h_close(H, ocells.hidden_chunked(cfg.cell, X, W, U, b))
+    model.close()
+
+
+def _sample_rows(N, S, seed):
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([np.arange(0, 96), np.arange(N - 96, N),
+                                     rng.integers(0, N, size=S)]))
+    return rows
+
+
+@pytest.mark.parametrize("name,q_short", [("cfg3", 12), ("cfg4", 8), ("cfg5", 10)])
+def test_full_size_configs_short_horizon_and_step_at_depth(elm, name, q_short):
+    """Full N in the benchmark's launch configuration; the oracle checks sampled rows.
+
+    These cells amplify a 1e-7 perturbation by orders of magnitude over the full Q, so exact
+    trajectories are compared on a short horizon, and single steps are compared at depth from
+    oracle states (saturated-state statistics at the real shape).
+    """
+    cfg = synthdata.get_config(name)
+    series, _, _ = synthdata.make_problem(cfg, materialise=False)
+    sd = torch.from_numpy(series).cuda()
+    N, Q, d, L = cfg.N, cfg.Q, cfg.d, cfg.L
+    Xv = torch.as_strided(sd, (N, Q, d), (d, d, 1))
+    model = elm.Model.create(cfg.cell, Q, d, L, cfg.m, cfg.seed, w_scale=cfg.w_scale,
+                             forget_bias=cfg.forget_bias, zero_bias=cfg.zero_bias)
+    W, U, b, _ = model.weights()
+    rows = _sample_rows(N, 1024, seed=1)
+    Xs = np.lib.stride_tricks.sliding_window_view(series, (Q, d))[rows, 0]
+
+    H = elm.hidden(model, Xv, Q_run=q_short)
+    torch.cuda.synchronize()
+    assert_h_close(H[torch.from_numpy(rows).cuda()].cpu().numpy(),
+                   ocells.hidden(cfg.cell, Xs, W, U, b, steps=q_short))
+
+    # two steps at depth: oracle state after Q-2 steps (rounded to float32) -> last two steps
+    depth = Q - 2
+    rows2 = rows[:512]
+    Xs2 = Xs[:512]
+    if cfg.cell == "lstm":
+        h, c = ocells.hidden_lstm(Xs2, W, U, b, steps=depth, return_cell=True)
+    else:
+        h, c = ocells.hidden(cfg.cell, Xs2, W, U, b, steps=depth), None
+    h32 = h.astype(np.float32)
+    c32 = None if c is None else c.astype(np.float32)
+    Xtail = torch.from_numpy(np.ascontiguousarray(Xs2[:, depth:, :])).cuda()
+    kw = dict(h0=torch.from_numpy(h32).cuda())
+    if c32 is not None:
+        kw["c0"] = torch.from_numpy(c32).cuda()
+    H2 = elm.hidden(model, Xtail, **kw).cpu().numpy()
+    ref2 = ocells.hidden(cfg.cell, Xs2[:, depth:, :], W, U, b, h0=h32,
+                         **({"c0": c32} if c32 is not None else {}))
+    assert_h_close(H2, ref2)
+    model.close()
