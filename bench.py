@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark of the ELM-RNN fit hot path on one MI355X.
+
+A "step" is one whole fit (weights from the seed -> hidden matrix H(Q) -> TSQR solve with
+refinement) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--no-cpu-baseline]
+
+Workload: the LSTM N = 4M, Q = 100, d = 8, L = 512, m = 2 configuration (the one the headline
+metric is quoted on); other configurations can be selected for study with --config.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synthdata  # noqa: E402
+
+GATES = {"elman": 1, "lstm": 4, "gru": 3}
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
+
+# HBM traffic of one hidden-matrix kernel launch, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by a copy kernel of known size (profiles/ holds the summaries these come from).
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def stage1_flops(cfg) -> float:
+    """Algorithmic flops of one hidden-matrix launch: 2 Q kL (L + d) per sample."""
+    return 2.0 * cfg.Q * GATES[cfg.cell] * cfg.L * (cfg.L + cfg.d) * cfg.N
+
+
+def cpu_baseline(cfg, budget_rows: int):
+    """The float64 oracle, as it stands, on a bounded row sample of the same workload."""
+    from oracle import fit as ofit
+    n = min(cfg.N, budget_rows)
+    series = synthdata.make_series(n + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
+    X, T = synthdata.make_windows(series, n, cfg.Q, cfg.m)
+    t0 = time.perf_counter()
+    ofit.fit(cfg.cell, X, T, cfg.L, cfg.seed, w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius,
+             forget_bias=cfg.forget_bias, zero_bias=cfg.zero_bias)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env))
+    return {"value": n / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": f"numpy float64 oracle fit (H build + Householder solve) on the first {n} "
+                      f"windows of {cfg.name} ({dt:.1f} s)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (the fit path is single-GPU; see DESIGN.md "
+              "for how it would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1911_13252_amd as elm
+
+    cfg = synthdata.get_config(args.config)
+    torch.cuda.set_device(0)
+    series = synthdata.make_series(cfg.N + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
+    sd = torch.from_numpy(series).cuda()
+    X = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1)).contiguous()   # materialised windows
+    T = sd[cfg.Q:cfg.Q + cfg.N, :cfg.m].contiguous()
+    H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
+    ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
+    kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
+              zero_bias=cfg.zero_bias, workspace=ws, H_out=H)
+
+    def step():
+        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)
+        st = res.stats
+        res.model.close()
+        return st
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats = [step() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * dt / args.steps
+    hidden_ms = float(np.mean([s.t_hidden_ms for s in stats]))     # HIP events on the launch stream
+    solve_ms = float(np.mean([s.t_solve_ms for s in stats]))
+    achieved = stage1_flops(cfg) / (hidden_ms * 1e-3) / 1e12
+    out = {
+        "metric": "ELM fit samples/sec (H build + TSQR solve) at 1 GPU",
+        "value": cfg.N * args.steps / dt,
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.cell} ELM-RNN fit, N={cfg.N}, Q={cfg.Q}, d={cfg.d}, "
+                               f"L={cfg.L}, m={cfg.m}, materialised windows resident in HBM",
+                   "hidden_ms": hidden_ms, "solve_ms": solve_ms,
+                   "hidden_samples_per_s": cfg.N / (hidden_ms * 1e-3),
+                   "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
+                   "rmse": stats[-1].rmse, "ne_resid": stats[-1].ne_resid},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                     "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"},
+    }
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
+                                 "cfg5": 4096}[cfg.name]
+        out["cpu_baseline"] = cpu_baseline(cfg, rows)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
