@@ -67,6 +67,11 @@ def main() -> int:
     ap.add_argument("--config", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
+    ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
+                                                     "workload string then names the reduced N)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE "
+                         "counters in rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (the fit path is single-GPU; see DESIGN.md "
@@ -77,6 +82,9 @@ def main() -> int:
     import paper_1911_13252_amd as elm
 
     cfg = synthdata.get_config(args.config)
+    if args.n > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, N=args.n)
     torch.cuda.set_device(0)
     series = synthdata.make_series(cfg.N + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
     sd = torch.from_numpy(series).cuda()
@@ -92,6 +100,13 @@ def main() -> int:
         st = res.stats
         res.model.close()
         return st
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written by one plain copy kernel
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -53,6 +53,10 @@ class Stats:
 
 
 def lib_path() -> str:
+    """In-tree library; ELMRNN_LIBRARY may name another build of the same sources (experiments)."""
+    override = os.environ.get("ELMRNN_LIBRARY")
+    if override:
+        return override
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libelmrnn.so")
 
 

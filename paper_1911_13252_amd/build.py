@@ -26,15 +26,15 @@ def _compile(src: str, extra=()) -> str:
     return obj
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
+def build_library(verbose: bool = False, extra=(), out: str = LIB_PATH) -> str:
     """Compile every source for gfx950 and link the shared library; returns its path."""
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(lambda s: _compile(s, extra), SOURCES))
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs],
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs],
                    check=True)
     if verbose:
-        print("built", LIB_PATH)
-    return LIB_PATH
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":

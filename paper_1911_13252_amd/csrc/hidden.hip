@@ -19,6 +19,14 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load through a buffer descriptor: the base and the wave-uniform byte offset stay in
+// scalar registers, only the 32-bit lane offset is a vector register (no 64-bit pointer math).
+__device__ __forceinline__ floatx4 buffer_load_x4(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff) {
+    const uintx4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 0);
+    return __builtin_bit_cast(floatx4, v);
+}
 
 constexpr int kThreads = 256;      // 4 wavefronts, one per SIMD
 constexpr int kXPT = 4;            // input values a thread can prefetch per step
@@ -33,6 +41,7 @@ struct HiddenArgs {
     float* C;
     int64_t N;
     int Q_run, d, L, R, KG, nJB;
+    unsigned wp_bytes;
 };
 
 __device__ __forceinline__ float sigmoid_f(float x) {
@@ -45,63 +54,85 @@ __device__ __forceinline__ float tanh_f(float x) {
 // acc[g][ms] += A(ms) . B(g) over all k-groups.
 //   A fragment of k-group kg, tile ms: lane (r = lane&31, half = lane>>5) holds
 //     Abuf[(ms*32 + r)*R + kg*8 + half*4 + e], e = 0..3      (one ds_read_b128)
-//   B fragment of k-group kg, gate g: lane holds 4 floats at bp[(kg*GT + g)*256 + e]
+//   B fragment of k-group kg, gate slot g (gate GA + g*GSTEP of GT): lane holds the 4 floats at
+//     byte wbase + (kg*GT + GA + g*GSTEP)*1024 + 16*lane
 //     = weight row kg*8 + half*4 + e, column (lane&31) of that gate's 32-column block.
 //   MFMA step e therefore contracts k-slots {kg*8+e, kg*8+4+e}; every k is covered once.
-template <int G, int GT, int MS, int PF>
+template <int G, int GT, int GA, int GSTEP, int MS, int PF>
 __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __restrict__ Abuf,
-                                         int R, const float* __restrict__ bp, int KG, int lane) {
+                                         int R, __amdgpu_buffer_rsrc_t wrs, unsigned wbase, int KG, int lane) {
+    const unsigned voff = (unsigned)lane * 16u;   // wbase: wave-uniform byte offset of this block's fragments
     const float* ap = Abuf + (lane & 31) * R + (lane >> 5) * 4;
-    // PF k-groups of weight fragments are kept in flight; the loads for group kg+PF are issued
-    // before the MFMAs of group kg so that their latency hides behind PF groups of matrix work.
+    // PF k-groups of weight fragments are in flight.  Slot u is consumed by the MFMAs of group
+    // kg+u and refilled, in place, with group kg+u+PF right after them, so every load has PF-1
+    // groups of matrix work to hide behind and no register copies are needed at the loop edge.
     floatx4 bq[PF][G];
+    // Drain every older vector-memory access first (s_waitcnt vmcnt(0)): the compiler's wait
+    // insertion then sees only the weight loads below as pending inside the loop and emits exact
+    // vmcnt(n) waits instead of draining the queue once per trip.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
-    for (int u = 0; u < PF; ++u)
+    for (int u = 0; u < PF; ++u) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            bq[u][g] = *reinterpret_cast<const floatx4*>(bp + ((size_t)u * GT + g) * 256);
+            bq[u][g] = buffer_load_x4(wrs, voff, wbase + (unsigned)(u * GT + GA + g * GSTEP) * 1024u);
+        __builtin_amdgcn_sched_barrier(0);      // issue order: oldest slot first
+    }
+    floatx4 a[MS];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) a[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * R);
 
-    for (int kg = 0; kg < KG; kg += PF) {
+    auto group = [&](int k, int u, bool refill) {
+        floatx4 an[MS];              // activation fragment of the next group
+        const int kn = (k + 1 < KG) ? (k + 1) : k;
 #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            if (kg + u < KG) {
-                floatx4 b[G];
+        for (int ms = 0; ms < MS; ++ms)
+            an[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * R + kn * 8);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int g = 0; g < G; ++g) b[g] = bq[u][g];
-                floatx4 a[MS];
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
-                    a[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * R + (kg + u) * 8);
-                // refill this slot with the group PF ahead (the packed buffer has a PF-group tail)
+                    acc[g][ms] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ms][e], bq[u][g][e], acc[g][ms],
+                                                                      0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (refill) {
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    bq[u][g] = *reinterpret_cast<const floatx4*>(
-                        bp + ((size_t)(kg + u + PF) * GT + g) * 256);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int g = 0; g < G; ++g)
-#pragma unroll
-                        for (int ms = 0; ms < MS; ++ms)
-                            acc[g][ms] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ms][e], b[g][e],
-                                                                              acc[g][ms], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int g = 0; g < G; ++g)
+                bq[u][g] = buffer_load_x4(wrs, voff, wbase + (unsigned)((k + PF) * GT + GA + g * GSTEP) * 1024u);
         }
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) a[ms] = an[ms];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    int kg = 0;
+    for (; kg + PF <= KG; kg += PF) {           // branch-free body: PF groups, PF refills
+#pragma unroll
+        for (int u = 0; u < PF; ++u) group(kg + u, u, true);
     }
+#pragma unroll
+    for (int u = 0; u < PF - 1; ++u)            // remaining KG % PF groups, nothing left to load
+        if (kg + u < KG) group(kg + u, u, false);
 }
 
 template <int CELL, int MS, int NCH>
 __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS;
-    constexpr int PF = (G >= 3) ? 2 : 4;
+    constexpr int PF = 4;
+    constexpr bool TWOPASS = (CELL == ELM_CELL_LSTM) && (NCH >= 3);
     extern __shared__ __align__(16) float lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // wave-uniform values are forced into scalar registers: weight addresses then live in SGPRs
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = p.L, R = p.R, d = p.d, KG = p.KG;
     const int64_t row0 = (int64_t)blockIdx.x * S;
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
     float* A0 = lds;               // [S][R]: h_{t-1} | x_t | 1 | 0...
     float* A1 = lds + S * R;       // GRU only: (r*h_{t-1}) | x_t | 1 | 0...
 
@@ -198,43 +229,82 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             for (int ch = 0; ch < NCH; ++ch) {
                 const int jb = ch * 4 + wave;
                 if (jb < p.nJB) {
-                    floatx16 acc[G][MS];
+                    const unsigned wbase = (unsigned)(jb * KG * G) * 1024u;
+                    if (TWOPASS) {
+                        // LSTM with many column chunks: two contractions of two gates each keep the
+                        // accumulators at 64 registers so that c and the pending h stay in registers
+                        floatx16 acc[2][MS];
+                        float ig_gg[MS][16];
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
+                        for (int g = 0; g < 2; ++g)
+#pragma unroll
+                            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
+                        contract<2, 4, 0, 3, MS, 6>(acc, A0, R, wrs, wbase, KG, lane);     // gates i, g
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                            for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                    const float* bp = p.Wp + (size_t)jb * KG * G * 256 + lane * 4;
-                    contract<G, G, MS, PF>(acc, A0, R, bp, KG, lane);
-#pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            if (CELL == ELM_CELL_ELMAN) {
-                                hn[ch][ms][i] = tanh_f(acc[0][ms][i]);
-                            } else {
-                                const float ig = sigmoid_f(acc[0][ms][i]);
-                                const float fg = sigmoid_f(acc[G > 1 ? 1 : 0][ms][i]);
-                                const float og = sigmoid_f(acc[G > 2 ? 2 : 0][ms][i]);
-                                const float gg = tanh_f(acc[G > 3 ? 3 : 0][ms][i]);
-                                const float c = fg * st[ch][ms][i] + ig * gg;
-                                st[ch][ms][i] = c;
-                                hn[ch][ms][i] = og * tanh_f(c);
+                            for (int i = 0; i < 16; ++i) {
+                                ig_gg[ms][i] = sigmoid_f(acc[0][ms][i]) * tanh_f(acc[1][ms][i]);
+                                acc[0][ms][i] = 0.0f;
+                                acc[1][ms][i] = 0.0f;
                             }
-                        }
+                        contract<2, 4, 1, 1, MS, 6>(acc, A0, R, wrs, wbase, KG, lane);     // gates f, o
+#pragma unroll
+                        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const float c = sigmoid_f(acc[0][ms][i]) * st[ch][ms][i] + ig_gg[ms][i];
+                                st[ch][ms][i] = c;
+                                hn[ch][ms][i] = sigmoid_f(acc[1][ms][i]) * tanh_f(c);
+                            }
+                    } else {
+                        floatx16 acc[G][MS];
+#pragma unroll
+                        for (int g = 0; g < G; ++g)
+#pragma unroll
+                            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
+                        contract<G, G, 0, 1, MS, PF>(acc, A0, R, wrs, wbase, KG, lane);
+#pragma unroll
+                        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                if (CELL == ELM_CELL_ELMAN) {
+                                    hn[ch][ms][i] = tanh_f(acc[0][ms][i]);
+                                } else {
+                                    const float ig = sigmoid_f(acc[0][ms][i]);
+                                    const float fg = sigmoid_f(acc[G > 1 ? 1 : 0][ms][i]);
+                                    const float og = sigmoid_f(acc[G > 2 ? 2 : 0][ms][i]);
+                                    const float gg = tanh_f(acc[G > 3 ? 3 : 0][ms][i]);
+                                    const float c = fg * st[ch][ms][i] + ig * gg;
+                                    st[ch][ms][i] = c;
+                                    hn[ch][ms][i] = og * tanh_f(c);
+                                }
+                            }
+                    }
                 }
             }
             __syncthreads();          // every wave has finished reading h_{t-1}
+            {
+                // lane base address, made opaque per step so that the 32*NCH store addresses are
+                // recomputed here (scalar row offsets) instead of being kept live across the unroll
+                int lane_base = (4 * (lane >> 5)) * R + col_in;
+                asm volatile("" : "+v"(lane_base));
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
-                const int col = jb * 32 + col_in;
-                if (jb < p.nJB && col < L) {
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const int jb = ch * 4 + wave;
+                    const int col = jb * 32 + col_in;
+                    if (jb < p.nJB && col < L) {
+                        float* dst = A0 + lane_base + jb * 32;
 #pragma unroll
-                    for (int ms = 0; ms < MS; ++ms)
+                        for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) A0[acc_row(ms, i) * R + col] = hn[ch][ms][i];
+                            for (int i = 0; i < 16; ++i)
+                                dst[(ms * 32 + 8 * (i >> 2) + (i & 3)) * R] = hn[ch][ms][i];
+                    }
                 }
             }
             if (more) {
@@ -255,8 +325,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                    const float* bp = p.Wp + (size_t)jb * KG * 3 * 256 + lane * 4;
-                    contract<2, 3, MS, 4>(acc, A0, R, bp, KG, lane);
+                    contract<2, 3, 0, 1, MS, 4>(acc, A0, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -279,8 +348,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) acc[0][ms][i] = 0.0f;
-                    const float* bp = p.Wp + ((size_t)jb * KG * 3 + 2) * 256 + lane * 4;
-                    contract<1, 3, MS, 4>(acc, A1, R, bp, KG, lane);
+                    contract<1, 3, 2, 1, MS, 4>(acc, A1, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -410,7 +478,7 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
     HiddenArgs a{};
     a.X = X; a.ldx_n = ldx_n; a.ldx_q = ldx_q; a.Wp = Wp; a.h0 = h0; a.c0 = c0;
     a.H = H; a.C = C; a.N = N; a.Q_run = Q_run; a.d = lay.d; a.L = lay.L; a.R = lay.R;
-    a.KG = lay.KG; a.nJB = lay.nJB;
+    a.KG = lay.KG; a.nJB = lay.nJB; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
     switch (lay.cell) {
         case ELM_CELL_ELMAN: return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, stream);
         case ELM_CELL_LSTM:  return launch_cell<ELM_CELL_LSTM>(ms, nch, a, N, lds_per_row, stream);
