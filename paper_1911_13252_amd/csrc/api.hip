@@ -54,8 +54,9 @@ double spectral_radius(const std::vector<double>& A, int n) {
     double nf = frobenius(B);
     if (nf == 0.0) return 0.0;
     for (double& v : B) v /= nf;
-    double log_rho = std::log(nf), w = 1.0;
-    for (int it = 0; it < 60; ++it) {
+    double log_rho = std::log(nf), w = 1.0, prev = -1.0;
+    int settled = 0;
+    for (int it = 0; it < 48; ++it) {       // 2^-48 * |log ||B^2||| is below double rounding of log rho
         std::fill(C.begin(), C.end(), 0.0);
         for (int i = 0; i < n; ++i)
             for (int k = 0; k < n; ++k) {
@@ -67,6 +68,14 @@ double spectral_radius(const std::vector<double>& A, int n) {
         const double nc = frobenius(C);
         if (nc == 0.0) return 0.0;       // nilpotent
         w *= 0.5;
+        // once ||B_i^2|| has stopped changing (B_i has converged to the dominant rank-one part)
+        // the rest of the series is geometric: sum_{k>i} 2^-k log nc = 2^-i log nc
+        settled = (std::fabs(nc - prev) <= 4e-16 * nc) ? settled + 1 : 0;
+        if (settled >= 2) {
+            log_rho += 2.0 * w * std::log(nc);
+            break;
+        }
+        prev = nc;
         log_rho += w * std::log(nc);
         for (double& v : C) v /= nc;
         B.swap(C);

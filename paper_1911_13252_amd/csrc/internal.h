@@ -34,6 +34,7 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
 struct SolvePlan {
     int64_t N;
     int L, m, n, np;       // n = L + m columns, np = n rounded up to 32
+    int block_rows;        // rows per folded block (64 or 128)
     int levels;            // number of fold launches (level 0 + combine levels)
     int groups[8];         // work-groups (= R factors produced) per level
     size_t off_R[2];       // ping-pong R-factor stacks (bytes from workspace base)

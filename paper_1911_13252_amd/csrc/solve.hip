@@ -271,33 +271,140 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const float* __restric
     }
 }
 
-// Sum the per-work-group partials in a fixed order; scal[0..2] = rss, sum H^2, ||g||^2.
+// Same contract as stream_kernel for m <= 4 and L <= 512, organised for HBM rate: one wavefront
+// owns a row at a time (lane l holds columns l, l+64, ...), beta and the gradient accumulators
+// live in registers, the row dot products are reduced with wavefront shuffles, and there is no
+// work-group barrier inside the row loop.
+template <int M, int MODE>
+__global__ __launch_bounds__(kThreads) void stream_rows_kernel(const float* __restrict__ H,
+                                                               const float* __restrict__ T, int64_t N, int L,
+                                                               int m, const double* __restrict__ beta,
+                                                               double* __restrict__ part,
+                                                               float* __restrict__ Y) {
+    constexpr int EPL = 8;                        // columns per lane: L <= 512
+    __shared__ double wsum[EPL * 64 * M + 2];     // in-group sum of the 4 waves' results
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double bt[EPL][M], gacc[EPL][M];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int jx = e * 64 + lane;
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+            bt[e][c] = (jx < L && c < m) ? beta[(size_t)jx * m + c] : 0.0;
+            gacc[e][c] = 0.0;
+        }
+    }
+    double rss = 0.0, h2 = 0.0;
+    const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t row = wave_id; row < N; row += nwaves) {
+        const float* hr = H + row * L;
+        float hv[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const int jx = e * 64 + lane;
+            hv[e] = (jx < L) ? hr[jx] : 0.0f;
+        }
+        double dot[M];
+#pragma unroll
+        for (int c = 0; c < M; ++c) dot[c] = 0.0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const double h = (double)hv[e];
+            if (MODE == 0) h2 = fma(h, h, h2);
+#pragma unroll
+            for (int c = 0; c < M; ++c) dot[c] = fma(h, bt[e][c], dot[c]);
+        }
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) dot[c] += __shfl_xor(dot[c], off);
+        }
+        if (MODE == 0) {
+            double res[M];
+#pragma unroll
+            for (int c = 0; c < M; ++c) {
+                res[c] = (c < m) ? (double)T[row * m + c] - dot[c] : 0.0;
+                if (lane == 0) rss = fma(res[c], res[c], rss);
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const double h = (double)hv[e];
+#pragma unroll
+                for (int c = 0; c < M; ++c) gacc[e][c] = fma(h, res[c], gacc[e][c]);
+            }
+        } else if (lane < m) {
+            double v = dot[0];
+#pragma unroll
+            for (int c = 1; c < M; ++c) v = (lane == c) ? dot[c] : v;
+            Y[row * m + lane] = (float)v;
+        }
+    }
+    if (MODE == 0) {
+        // fixed-order sum over the 4 waves (wave 0 first), then one partial record per work-group
+        for (int off = 32; off > 0; off >>= 1) h2 += __shfl_xor(h2, off);
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e)
+#pragma unroll
+                    for (int c = 0; c < M; ++c) {
+                        const int idx = (e * 64 + lane) * M + c;
+                        wsum[idx] = (w == 0) ? gacc[e][c] : wsum[idx] + gacc[e][c];
+                    }
+                if (lane == 0) {
+                    wsum[EPL * 64 * M] = (w == 0) ? rss : wsum[EPL * 64 * M] + rss;
+                    wsum[EPL * 64 * M + 1] = (w == 0) ? h2 : wsum[EPL * 64 * M + 1] + h2;
+                }
+            }
+            __syncthreads();
+        }
+        double* mypart = part + (size_t)blockIdx.x * ((size_t)L * m + 2);
+        for (int idx = tid; idx < L * m; idx += kThreads) {
+            const int jx = idx / m, c = idx - jx * m;
+            mypart[idx] = wsum[jx * M + c];
+        }
+        if (tid < 2) mypart[(size_t)L * m + tid] = wsum[EPL * 64 * M + tid];
+    }
+}
+
+// Sum the per-work-group partials in a fixed order.  Thread (o, q) of a work-group adds the
+// partials w = q, q+8, ... of output o; the 8 sub-sums are then added in order.
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part,
                                                                    int nparts, int L, int m,
                                                                    double* small) {
+    __shared__ double sub[8][32];
+    const int tid = threadIdx.x, ol = tid & 31, q = tid >> 5;
+    const int nout = L * m + 2;
+    const int o = blockIdx.x * 32 + ol;
+    double s = 0.0;
+    if (o < nout)
+        for (int w = q; w < nparts; w += 8) s += part[(size_t)w * nout + o];
+    sub[q][ol] = s;
+    __syncthreads();
+    if (q == 0 && o < nout) {
+        double t = 0.0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t += sub[r][ol];
+        if (o < L * m) small[SmallArea::grad(L, m) + o] = t;
+        else small[SmallArea::scal(L, m) + (o - L * m)] = t;       // [0] rss, [1] sum H^2
+    }
+}
+
+// scal[2] = ||g||_F^2
+__global__ __launch_bounds__(kThreads) void grad_norm_kernel(int L, int m, double* small) {
     __shared__ double sred[kThreads];
     const int tid = threadIdx.x;
-    const int nout = L * m + 2;
-    double* grad = small + SmallArea::grad(L, m);
-    double* scal = small + SmallArea::scal(L, m);
+    const double* grad = small + SmallArea::grad(L, m);
     double g2 = 0.0;
-    for (int o = tid; o < nout; o += kThreads) {
-        double s = 0.0;
-        for (int w = 0; w < nparts; ++w) s += part[(size_t)w * nout + o];
-        if (o < L * m) {
-            grad[o] = s;
-            g2 += s * s;
-        } else {
-            scal[o - L * m] = s;
-        }
-    }
+    for (int o = tid; o < L * m; o += kThreads) g2 = fma(grad[o], grad[o], g2);
     sred[tid] = g2;
     __syncthreads();
-    for (int s = kThreads / 2; s > 0; s >>= 1) {
-        if (tid < s) sred[tid] += sred[tid + s];
+    for (int st = kThreads / 2; st > 0; st >>= 1) {
+        if (tid < st) sred[tid] += sred[tid + st];
         __syncthreads();
     }
-    if (tid == 0) scal[2] = sred[0];
+    if (tid == 0) small[SmallArea::scal(L, m) + 2] = sred[0];
 }
 
 __global__ void export_beta_kernel(const double* __restrict__ beta, int count, float* b32, double* b64) {
@@ -314,7 +421,7 @@ size_t stream_lds_bytes(int L, int M) {
 
 int stream_grid(int64_t N) {
     const int64_t ntiles = (N + kTileRows - 1) / kTileRows;
-    return (int)(ntiles < 1024 ? ntiles : 1024);
+    return (int)(ntiles < 1024 ? ntiles : 1024);      // <= 1024 partial records in the workspace
 }
 
 template <int MODE>
@@ -323,6 +430,23 @@ hipError_t launch_stream(const float* H, const float* T, int64_t N, int L, int m
     const int grid = stream_grid(N);
     int M = 1;
     while (M < m) M *= 2;
+    if (M <= 4 && L <= 512) {       // register-resident variant
+        switch (M) {
+            case 1:
+                hipLaunchKernelGGL((stream_rows_kernel<1, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
+                                   L, m, beta, part, Y);
+                break;
+            case 2:
+                hipLaunchKernelGGL((stream_rows_kernel<2, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
+                                   L, m, beta, part, Y);
+                break;
+            default:
+                hipLaunchKernelGGL((stream_rows_kernel<4, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
+                                   L, m, beta, part, Y);
+                break;
+        }
+        return hipGetLastError();
+    }
     const size_t lds = stream_lds_bytes(L, M);
 #define ELM_STREAM_CASE(MM)                                                                         \
     case MM: {                                                                                      \
@@ -334,9 +458,6 @@ hipError_t launch_stream(const float* H, const float* T, int64_t N, int L, int m
         return hipGetLastError();                                                                   \
     }
     switch (M) {
-        ELM_STREAM_CASE(1)
-        ELM_STREAM_CASE(2)
-        ELM_STREAM_CASE(4)
         ELM_STREAM_CASE(8)
         ELM_STREAM_CASE(16)
         default: return hipErrorInvalidValue;
@@ -359,8 +480,12 @@ hipError_t launch_residual_pass(const SolvePlan& pl, const float* H, const float
     double* part = reinterpret_cast<double*>(base + pl.off_part);
     hipError_t e = launch_stream<0>(H, T, pl.N, pl.L, pl.m, small + SmallArea::BETA, part, nullptr, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kThreads), 0, stream, part,
+    const int nout = pl.L * pl.m + 2;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((nout + 31) / 32), dim3(kThreads), 0, stream, part,
                        stream_grid(pl.N), pl.L, pl.m, small);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(grad_norm_kernel, dim3(1), dim3(kThreads), 0, stream, pl.L, pl.m, small);
     return hipGetLastError();
 }
 

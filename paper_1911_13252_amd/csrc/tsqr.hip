@@ -25,7 +25,6 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kRows = 64;       // rows per folded block
 constexpr int kNB = 32;         // panel width = MFMA tile width
 constexpr int kFan = 4;         // R factors folded by one work-group in a combine level
 
@@ -42,21 +41,35 @@ struct FoldArgs {
     int np, ldb;
 };
 
+// value of x in lane `src` (compile-time constant), delivered through a scalar register
+__device__ __forceinline__ float lane_bcast(float x, int src) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src));
+}
+
 // row index inside a 32x32 accumulator tile held in register q by a lane of half h
 __device__ __forceinline__ int rho(int q) { return 8 * (q >> 2) + (q & 3); }
 
+constexpr int kTs = 33;      // row stride of the T factor in LDS
+constexpr int kGs = 36;      // row stride of the Gram matrix in LDS (16-byte aligned rows)
+
+// BR = rows per folded block (64 or 128).  Taller blocks halve the number of sequential
+// Householder steps per input row; they are used whenever the block fits in LDS.
+template <int BR>
 __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
+    constexpr int RPT = BR / 8;      // rows of a panel column held by one lane
+    constexpr int MT = BR / 32;      // 32-row accumulator tiles per block
     extern __shared__ __align__(16) float lds[];
     const int np = a.np, ldb = a.ldb, NP = np / kNB;
-    float* Bs = lds;                           // [64][ldb]
-    float* Ts = Bs + kRows * ldb;              // [32][33]  compact-WY T
-    float* Gs = Ts + 32 * 33;                  // [32][33]  strict upper part of V_B^T V_B
-    float* red = Gs + 32 * 33;                 // [2][4][32] cross-wave partial sums
+    float* Bs = lds;                           // [BR][ldb]
+    float* Gs = Bs + ((BR * ldb + 3) & ~3);    // [32][36] strict upper part of V_B^T V_B
+    float* Ts = Gs + 32 * kGs;                 // [32][33] compact-WY T
+    float* red = Ts + 32 * kTs;                // [2][4][32] cross-wave partial sums
     float* taus = red + 2 * 4 * 32;            // [32]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = tid & 31;          // panel column of this lane
-    const int g = tid >> 5;          // row group: rows 8g .. 8g+7
+    const int g = tid >> 5;          // row group: rows RPT*g .. RPT*g + RPT-1
     const int half = lane >> 5;
     float* R = a.Rout + (size_t)blockIdx.x * np * np;
 
@@ -68,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
         blk_begin = (int)(((int64_t)a.nblocks * blockIdx.x) / gridDim.x);
         blk_end = (int)(((int64_t)a.nblocks * (blockIdx.x + 1)) / gridDim.x);
     } else {
-        per_r = (np + kRows - 1) / kRows;                     // 64-row slices per R factor
+        per_r = (np + BR - 1) / BR;                           // BR-row slices per R factor
         const int r_begin = blockIdx.x * kFan;
         const int r_end = min(r_begin + kFan, a.nprev);
         blk_begin = r_begin * per_r;
@@ -80,8 +93,8 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
         // ---- load the block into LDS (zero padded)
         int p0 = 0;
         if (!a.combine) {
-            const int64_t r0 = (int64_t)blk * kRows;
-            for (int idx = tid; idx < kRows * np; idx += kThreads) {
+            const int64_t r0 = (int64_t)blk * BR;
+            for (int idx = tid; idx < BR * np; idx += kThreads) {
                 const int r = idx / np, c = idx - r * np;
                 const int64_t row = r0 + r;
                 float v = 0.0f;
@@ -94,9 +107,9 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
         } else {
             const int ri = blk / per_r, slice = blk - ri * per_r;
             const float* src = a.src0 + (size_t)ri * np * np;
-            const int rbase = slice * kRows;
+            const int rbase = slice * BR;
             p0 = rbase / kNB;                                   // columns left of the slice are zero
-            for (int idx = tid; idx < kRows * np; idx += kThreads) {
+            for (int idx = tid; idx < BR * np; idx += kThreads) {
                 const int r = idx / np, c = idx - r * np;
                 const int row = rbase + r;
                 Bs[r * ldb + c] = (row < np) ? src[(size_t)row * np + c] : 0.0f;
@@ -104,56 +117,65 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
         }
         __syncthreads();
 
+        // diagonal block of R for the first panel; later ones are fetched one panel ahead (a
+        // panel's trailing update never touches the rows of R that the next panel factors)
+        float rdv[32];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(p0 * kNB + k) * np + p0 * kNB + j];
+
         for (int p = p0; p < NP; ++p) {
             const int kp = p * kNB;
             // ================= panel factorisation =================
-            float pv[8], rdv[32];
+            float pv[RPT];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) pv[i] = Bs[(8 * g + i) * ldb + kp + j];
-#pragma unroll
-            for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(kp + k) * np + kp + j];
+            for (int i = 0; i < RPT; ++i) pv[i] = Bs[(RPT * g + i) * ldb + kp + j];
 
 #pragma unroll
             for (int k = 0; k < 32; ++k) {
-                const int srcl = k + (lane & 32);
-                float xk[8];
+                // column k of this lane's row group: broadcast from lane k (lower half-wave) or
+                // 32 + k (upper half-wave) through scalar registers
+                float xk[RPT];
                 float s = 0.0f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    xk[i] = __shfl(pv[i], srcl);
+                for (int i = 0; i < RPT; ++i) {
+                    const float lo = lane_bcast(pv[i], k);
+                    const float hi = lane_bcast(pv[i], 32 + k);
+                    xk[i] = half ? hi : lo;
                     s = fmaf(xk[i], pv[i], s);
                 }
                 s += __shfl_xor(s, 32);
                 float* rb = red + (k & 1) * 128;
                 if (half == 0) rb[wave * 32 + j] = s;
-                const float x0 = __shfl(rdv[k], srcl);
+                const float x0 = lane_bcast(rdv[k], k);     // every copy is identical
                 __syncthreads();
                 const float sj = (rb[j] + rb[32 + j]) + (rb[64 + j] + rb[96 + j]);
                 const float sigma = (rb[k] + rb[32 + k]) + (rb[64 + k] + rb[96 + k]);
                 float alpha = x0, tau = 0.0f, f = 0.0f;
-                if (sigma > 0.0f) {
-                    const float nrm = sqrtf(fmaf(x0, x0, sigma));
+                const float nrm2 = fmaf(x0, x0, sigma);
+                // Columns whose remaining mass is below 1e-30 are left alone (identity reflector):
+                // they arise as rounding residue of residue when a block has fewer rows than
+                // columns, and the hardware sqrt / reciprocal flush denormals.
+                if (sigma > 0.0f && nrm2 > 1e-30f) {
+                    // hardware sqrt / reciprocal (1 ulp): a reflector built from slightly rounded
+                    // tau and 1/(x0 - alpha) is orthogonal to the same order as float32 rounding
+                    const float nrm = __builtin_amdgcn_sqrtf(nrm2);
                     alpha = (x0 >= 0.0f) ? -nrm : nrm;
-                    tau = (alpha - x0) / alpha;
-                    f = 1.0f / (x0 - alpha);
+                    tau = (alpha - x0) * __builtin_amdgcn_rcpf(alpha);
+                    f = __builtin_amdgcn_rcpf(x0 - alpha);
                 }
-                if (j == k) {
-                    rdv[k] = alpha;
+                // branch-free update: lanes j > k apply the reflector, lane j == k stores it
+                const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
+                rdv[k] = (j == k) ? alpha : rdv[k] - w;
+                const float fw = f * w;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) pv[i] = xk[i] * f;
-                    if (g == 0) taus[k] = tau;
-                } else if (j > k) {
-                    const float w = tau * fmaf(f, sj, rdv[k]);
-                    rdv[k] -= w;
-                    const float fw = f * w;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) pv[i] = fmaf(-xk[i], fw, pv[i]);
-                } else if (g == 0) {
-                    Gs[j * 33 + k] = f * sj;      // v_j . v_k for the finished reflector j < k
+                for (int i = 0; i < RPT; ++i) pv[i] = (j == k) ? xk[i] * f : fmaf(-xk[i], fw, pv[i]);
+                if (g == 0) {
+                    if (j == k) taus[k] = tau;
+                    if (j < k) Gs[j * kGs + k] = f * sj;      // v_j . v_k for the finished reflector j
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Bs[(8 * g + i) * ldb + kp + j] = pv[i];
+            for (int i = 0; i < RPT; ++i) Bs[(RPT * g + i) * ldb + kp + j] = pv[i];
             if (g == 0) {
 #pragma unroll
                 for (int k = 0; k < 32; ++k)
@@ -162,49 +184,71 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
             __syncthreads();
             if (p + 1 == NP) break;       // last panel: nothing to the right
 
-            // ================= T factor (forward, column by column) =================
+            // next panel's diagonal block of R: in flight during the T factor and trailing update
+#pragma unroll
+            for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(kp + kNB + k) * np + kp + kNB + j];
+
+            // ================= T factor =================
+            // T^-1 = diag(1/tau) + striu(V^T V): column k of T by back substitution, one lane per
+            // column; t[l] = 0 for l > k makes every lane run the same instruction stream.
             if (wave == 0 && half == 0) {
-                float trow[32];
+                float t[32], tv[32];
 #pragma unroll
-                for (int k = 0; k < 32; ++k) trow[k] = 0.0f;
-#pragma unroll
-                for (int k = 0; k < 32; ++k) {
-                    float acc = 0.0f;
-#pragma unroll
-                    for (int l = 0; l < k; ++l) acc = fmaf(trow[l], Gs[l * 33 + k], acc);
-                    const float tk = taus[k];
-                    trow[k] = (j == k) ? tk : ((j < k) ? -tk * acc : 0.0f);
+                for (int l = 0; l < 32; ++l) {
+                    tv[l] = taus[l];
+                    t[l] = 0.0f;
                 }
 #pragma unroll
-                for (int k = 0; k < 32; ++k) Ts[j * 33 + k] = trow[k];
+                for (int l = 0; l < 32; ++l) t[l] = (l == j) ? tv[l] : 0.0f;
+#pragma unroll
+                for (int i = 30; i >= 0; --i) {
+                    float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+                    for (int l = i + 1; l < 32; ++l) {
+                        const float gv = Gs[i * kGs + l];       // same address in every lane
+                        if ((l - i) & 1) s0 = fmaf(gv, t[l], s0); else s1 = fmaf(gv, t[l], s1);
+                    }
+                    t[i] = (i < j) ? -tv[i] * (s0 + s1) : t[i];
+                }
+#pragma unroll
+                for (int i = 0; i < 32; ++i) Ts[i * kTs + j] = t[i];
             }
             __syncthreads();
 
             // ================= trailing update on MFMA =================
             {
                 const int c = lane & 31;
-                float va1[32], va3[2][16], tq[16];
+                float va1[BR / 2], va3[MT][16], tq[16];
 #pragma unroll
-                for (int s = 0; s < 32; ++s) va1[s] = Bs[(2 * s + half) * ldb + kp + c];
+                for (int s = 0; s < BR / 2; ++s) va1[s] = Bs[(2 * s + half) * ldb + kp + c];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int q = 0; q < 16; ++q)
                         va3[mt][q] = Bs[(mt * 32 + c) * ldb + kp + rho(q) + 4 * half];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) tq[q] = Ts[(rho(q) + 4 * half) * 33 + c];
+                for (int q = 0; q < 16; ++q) tq[q] = Ts[(rho(q) + 4 * half) * kTs + c];
 
-                for (int ct = p + 1 + wave; ct < NP; ct += 4) {
-                    const int cc = ct * kNB + c;
-                    floatx16 crv, acc, acc2;
+                int ct = p + 1 + wave;
+                floatx16 crv;
+                if (ct < NP) {
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) {
-                        crv[q] = R[(size_t)(kp + rho(q) + 4 * half) * np + cc];
-                        acc[q] = crv[q];
-                        acc2[q] = 0.0f;
+                    for (int q = 0; q < 16; ++q)
+                        crv[q] = R[(size_t)(kp + rho(q) + 4 * half) * np + ct * kNB + c];
+                }
+                for (; ct < NP; ct += 4) {
+                    const int cc = ct * kNB + c;
+                    floatx16 acc = crv, acc2, crn;
+                    // R tile of this wave's next column tile: its latency hides behind the MFMAs
+                    if (ct + 4 < NP) {
+#pragma unroll
+                        for (int q = 0; q < 16; ++q)
+                            crn[q] = R[(size_t)(kp + rho(q) + 4 * half) * np + cc + 4 * kNB];
                     }
 #pragma unroll
-                    for (int s = 0; s < 32; ++s)
+                    for (int q = 0; q < 16; ++q) acc2[q] = 0.0f;
+#pragma unroll
+                    for (int s = 0; s < BR / 2; ++s)
                         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va1[s], Bs[(2 * s + half) * ldb + cc],
                                                                    acc, 0, 0, 0);
 #pragma unroll
@@ -216,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
                         acc2[q] = -acc2[q];
                     }
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) {
+                    for (int mt = 0; mt < MT; ++mt) {
                         floatx16 cb;
 #pragma unroll
                         for (int q = 0; q < 16; ++q)
@@ -228,6 +272,7 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
                         for (int q = 0; q < 16; ++q)
                             Bs[(mt * 32 + rho(q) + 4 * half) * ldb + cc] = cb[q];
                     }
+                    crv = crn;
                 }
             }
             __syncthreads();
@@ -236,9 +281,9 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
     }
 }
 
-size_t fold_lds_bytes(int np) {
+size_t fold_lds_bytes(int np, int br) {
     const int ldb = np + 1;
-    return ((size_t)kRows * ldb + 2 * 32 * 33 + 2 * 4 * 32 + 32) * sizeof(float);
+    return ((size_t)((br * ldb + 3) & ~3) + 32 * kGs + 32 * kTs + 2 * 4 * 32 + 32) * sizeof(float);
 }
 
 }  // namespace
@@ -248,7 +293,9 @@ SolvePlan make_solve_plan(int64_t N, int L, int m) {
     pl.N = N; pl.L = L; pl.m = m;
     pl.n = L + m;
     pl.np = (pl.n + 31) / 32 * 32;
-    const int64_t nblocks = (N + kRows - 1) / kRows;
+    // 128-row blocks when the padded width allows it (LDS) and there are enough rows for them
+    pl.block_rows = (fold_lds_bytes(pl.np, 128) <= 160 * 1024 && N >= 128 * 64) ? 128 : 64;
+    const int64_t nblocks = (N + pl.block_rows - 1) / pl.block_rows;
     int64_t g0 = (nblocks + 3) / 4;
     if (g0 < 1) g0 = 1;
     if (g0 > 256) g0 = 256;
@@ -271,9 +318,18 @@ SolvePlan make_solve_plan(int64_t N, int L, int m) {
 
 hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void* ws, float** R_final,
                        hipStream_t stream) {
-    const size_t lds = fold_lds_bytes(pl.np);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tsqr_fold_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int dev = 0, lds_max = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return e;
+    // 128-row blocks whenever they fit in LDS and the input is tall enough to keep the grid busy
+    const bool tall = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max && pl.block_rows == 128;
+    const int br = tall ? 128 : 64;
+    const size_t lds = fold_lds_bytes(pl.np, br);
+    auto kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     char* base = static_cast<char*>(ws);
     FoldArgs a{};
@@ -285,7 +341,7 @@ hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void
             a.src0 = H; a.ld0 = pl.L; a.nc0 = pl.L;
             a.src1 = T; a.ld1 = pl.m; a.nc1 = pl.m;
             a.nrows = pl.N;
-            a.nblocks = (int)((pl.N + kRows - 1) / kRows);
+            a.nblocks = (int)((pl.N + br - 1) / br);
             a.combine = 0; a.nprev = 0;
         } else {
             a.src0 = reinterpret_cast<const float*>(base + pl.off_R[(lvl - 1) & 1]);
@@ -295,7 +351,7 @@ hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void
             a.combine = 1; a.nprev = pl.groups[lvl - 1];
         }
         a.Rout = out;
-        hipLaunchKernelGGL(tsqr_fold_kernel, dim3(pl.groups[lvl]), dim3(kThreads), lds, stream, a);
+        hipLaunchKernelGGL(kern, dim3(pl.groups[lvl]), dim3(kThreads), lds, stream, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         *R_final = out;
