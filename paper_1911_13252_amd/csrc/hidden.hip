@@ -50,7 +50,6 @@ __device__ __forceinline__ float sigmoid_f(float x) {
 __device__ __forceinline__ float tanh_f(float x) {
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x));
 }
-
 // acc[g][ms] += A(ms) . B(g) over all k-groups.
 //   A fragment of k-group kg, tile ms: lane (r = lane&31, half = lane>>5) holds
 //     Abuf[(ms*32 + r)*R + kg*8 + half*4 + e], e = 0..3      (one ds_read_b128)
@@ -58,17 +57,13 @@ __device__ __forceinline__ float tanh_f(float x) {
 //     byte wbase + (kg*GT + GA + g*GSTEP)*1024 + 16*lane
 //     = weight row kg*8 + half*4 + e, column (lane&31) of that gate's 32-column block.
 //   MFMA step e therefore contracts k-slots {kg*8+e, kg*8+4+e}; every k is covered once.
-template <int G, int GT, int GA, int GSTEP, int MS, int PF>
-__device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __restrict__ Abuf,
-                                         int R, __amdgpu_buffer_rsrc_t wrs, unsigned wbase, int KG, int lane) {
-    const unsigned voff = (unsigned)lane * 16u;   // wbase: wave-uniform byte offset of this block's fragments
-    const float* ap = Abuf + (lane & 31) * R + (lane >> 5) * 4;
-    // PF k-groups of weight fragments are in flight.  Slot u is consumed by the MFMAs of group
-    // kg+u and refilled, in place, with group kg+u+PF right after them, so every load has PF-1
-    // groups of matrix work to hide behind and no register copies are needed at the loop edge.
-    floatx4 bq[PF][G];
+// Fill all PF slots of the weight-fragment queue with k-groups 0..PF-1 of one contraction.
+template <int G, int GT, int GA, int GSTEP, int PF>
+__device__ __forceinline__ void prefetch_weights(floatx4 (&bq)[PF][G], __amdgpu_buffer_rsrc_t wrs,
+                                                 unsigned wbase, int lane) {
+    const unsigned voff = (unsigned)lane * 16u;
     // Drain every older vector-memory access first (s_waitcnt vmcnt(0)): the compiler's wait
-    // insertion then sees only the weight loads below as pending inside the loop and emits exact
+    // insertion then sees only these loads as pending inside the contraction loop and emits exact
     // vmcnt(n) waits instead of draining the queue once per trip.
     __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
@@ -78,6 +73,18 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
             bq[u][g] = buffer_load_x4(wrs, voff, wbase + (unsigned)(u * GT + GA + g * GSTEP) * 1024u);
         __builtin_amdgcn_sched_barrier(0);      // issue order: oldest slot first
     }
+}
+
+// The contraction proper; bq must hold k-groups 0..PF-1 (prefetch_weights).
+// PF k-groups of weight fragments are in flight.  Slot u is consumed by the MFMAs of group kg+u
+// and refilled, in place, with group kg+u+PF right after them, so every load has PF-1 groups of
+// matrix work to hide behind and no register copies are needed at the loop edge.
+template <int G, int GT, int GA, int GSTEP, int MS, int PF>
+__device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], floatx4 (&bq)[PF][G],
+                                              const float* __restrict__ Abuf, int R,
+                                              __amdgpu_buffer_rsrc_t wrs, unsigned wbase, int KG, int lane) {
+    const unsigned voff = (unsigned)lane * 16u;   // wbase: wave-uniform byte offset of this block's fragments
+    const float* ap = Abuf + (lane & 31) * R + (lane >> 5) * 4;
     floatx4 a[MS];
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms) a[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * R);
@@ -109,13 +116,25 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
     };
 
     int kg = 0;
-    for (; kg + PF <= KG; kg += PF) {           // branch-free body: PF groups, PF refills
+    for (; kg + 2 * PF <= KG; kg += PF) {       // branch-free body: PF groups, PF refills
 #pragma unroll
         for (int u = 0; u < PF; ++u) group(kg + u, u, true);
+    }
+    for (; kg + PF <= KG; kg += PF) {           // last full trip: refill only what is still needed
+#pragma unroll
+        for (int u = 0; u < PF; ++u) group(kg + u, u, kg + u + PF < KG);
     }
 #pragma unroll
     for (int u = 0; u < PF - 1; ++u)            // remaining KG % PF groups, nothing left to load
         if (kg + u < KG) group(kg + u, u, false);
+}
+
+template <int G, int GT, int GA, int GSTEP, int MS, int PF>
+__device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __restrict__ Abuf,
+                                         int R, __amdgpu_buffer_rsrc_t wrs, unsigned wbase, int KG, int lane) {
+    floatx4 bq[PF][G];
+    prefetch_weights<G, GT, GA, GSTEP, PF>(bq, wrs, wbase, lane);
+    contract_main<G, GT, GA, GSTEP, MS, PF>(acc, bq, Abuf, R, wrs, wbase, KG, lane);
 }
 
 template <int CELL, int MS, int NCH>
@@ -217,6 +236,10 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     }
     __syncthreads();
 
+    floatx4 bq2[6][2];         // weight-fragment queue of the two-pass LSTM path (lives across phases)
+    if (TWOPASS && wave < p.nJB)
+        prefetch_weights<2, 4, 0, 3, 6>(bq2, wrs, (unsigned)(wave * KG * G) * 1024u, lane);
+
     for (int t = 0; t < p.Q_run; ++t) {
         if (CELL == ELM_CELL_GRU) {
             if (x_prefetch) store_x(A1); else copy_x_direct(t, A1);
@@ -241,7 +264,11 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                                 for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                        contract<2, 4, 0, 3, MS, 6>(acc, A0, R, wrs, wbase, KG, lane);     // gates i, g
+                        // the weight queue of each contraction is filled one phase early (before the
+                        // point-wise work of the previous contraction), so the first MFMA never waits
+                        const int jn = ((ch + 1 < NCH) && ((ch + 1) * 4 + wave < p.nJB)) ? jb + 4 : wave;
+                        contract_main<2, 4, 0, 3, MS, 6>(acc, bq2, A0, R, wrs, wbase, KG, lane);   // gates i, g
+                        prefetch_weights<2, 4, 1, 1, 6>(bq2, wrs, wbase, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -250,7 +277,8 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                                 acc[0][ms][i] = 0.0f;
                                 acc[1][ms][i] = 0.0f;
                             }
-                        contract<2, 4, 1, 1, MS, 6>(acc, A0, R, wrs, wbase, KG, lane);     // gates f, o
+                        contract_main<2, 4, 1, 1, MS, 6>(acc, bq2, A0, R, wrs, wbase, KG, lane);   // gates f, o
+                        prefetch_weights<2, 4, 0, 3, 6>(bq2, wrs, (unsigned)(jn * KG * G) * 1024u, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
