@@ -137,7 +137,9 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
     contract_main<G, GT, GA, GSTEP, MS, PF>(acc, bq, Abuf, R, wrs, wbase, KG, lane);
 }
 
-template <int CELL, int MS, int NCH>
+// STAGE > 0: that many of a lane's pending new-h values (those of the first column chunk) wait in
+// spare LDS instead of registers; used by the largest LSTM variants, which otherwise spill.
+template <int CELL, int MS, int NCH, int STAGE>
 __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS;
@@ -154,6 +156,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
         const_cast<float*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
     float* A0 = lds;               // [S][R]: h_{t-1} | x_t | 1 | 0...
     float* A1 = lds + S * R;       // GRU only: (r*h_{t-1}) | x_t | 1 | 0...
+    float* stage = lds + S * R + tid;   // STAGE > 0: [STAGE][256] behind the operand, one column per thread
 
     // accumulator element (ms, i) of this lane: sample row, hidden column inside the block
     const int col_in = lane & 31;
@@ -285,7 +288,9 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                             for (int i = 0; i < 16; ++i) {
                                 const float c = sigmoid_f(acc[0][ms][i]) * st[ch][ms][i] + ig_gg[ms][i];
                                 st[ch][ms][i] = c;
-                                hn[ch][ms][i] = sigmoid_f(acc[1][ms][i]) * tanh_f(c);
+                                const float hv = sigmoid_f(acc[1][ms][i]) * tanh_f(c);
+                                if (ch == 0 && ms * 16 + i < STAGE) stage[(ms * 16 + i) * kThreads] = hv;
+                                else hn[ch][ms][i] = hv;
                             }
                     } else {
                         floatx16 acc[G][MS];
@@ -331,7 +336,9 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i)
-                                dst[(ms * 32 + 8 * (i >> 2) + (i & 3)) * R] = hn[ch][ms][i];
+                                dst[(ms * 32 + 8 * (i >> 2) + (i & 3)) * R] =
+                                    (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads]
+                                                                     : hn[ch][ms][i];
                     }
                 }
             }
@@ -419,9 +426,9 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     }
 }
 
-template <int CELL, int MS, int NCH>
+template <int CELL, int MS, int NCH, int STAGE>
 hipError_t launch_variant(const HiddenArgs& a, int64_t tiles, size_t lds_bytes, hipStream_t stream) {
-    auto kern = hidden_kernel<CELL, MS, NCH>;
+    auto kern = hidden_kernel<CELL, MS, NCH, STAGE>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
@@ -429,25 +436,35 @@ hipError_t launch_variant(const HiddenArgs& a, int64_t tiles, size_t lds_bytes, 
     return hipGetLastError();
 }
 
+constexpr int kStage = 24;      // staged values per lane: 24 KB of LDS per work-group
+
 template <int CELL, int MS>
-hipError_t launch_nch(int nch, const HiddenArgs& a, int64_t tiles, size_t lds, hipStream_t s) {
+hipError_t launch_nch(int nch, const HiddenArgs& a, int64_t tiles, size_t lds, size_t lds_max,
+                      hipStream_t s) {
+    // the two-pass LSTM variants take the LDS staging when the operand leaves room for it
+    const size_t staged = lds + (size_t)kStage * kThreads * sizeof(float);
+    const bool stage = (CELL == ELM_CELL_LSTM) && MS == 2 && nch >= 3 && staged <= lds_max;
     switch (nch) {
-        case 1: return launch_variant<CELL, MS, 1>(a, tiles, lds, s);
-        case 2: return launch_variant<CELL, MS, 2>(a, tiles, lds, s);
-        case 3: return launch_variant<CELL, MS, 3>(a, tiles, lds, s);
-        case 4: return launch_variant<CELL, MS, 4>(a, tiles, lds, s);
+        case 1: return launch_variant<CELL, MS, 1, 0>(a, tiles, lds, s);
+        case 2: return launch_variant<CELL, MS, 2, 0>(a, tiles, lds, s);
+        case 3:
+            if (stage) return launch_variant<CELL, MS, 3, (CELL == ELM_CELL_LSTM && MS == 2) ? kStage : 0>(a, tiles, staged, s);
+            return launch_variant<CELL, MS, 3, 0>(a, tiles, lds, s);
+        case 4:
+            if (stage) return launch_variant<CELL, MS, 4, (CELL == ELM_CELL_LSTM && MS == 2) ? kStage : 0>(a, tiles, staged, s);
+            return launch_variant<CELL, MS, 4, 0>(a, tiles, lds, s);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <int CELL>
 hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t lds_per_row,
-                       hipStream_t s) {
+                       size_t lds_max, hipStream_t s) {
     const int S = 32 * ms;
     const int64_t tiles = (N + S - 1) / S;
     const size_t lds = lds_per_row * S;
-    if (ms == 2) return launch_nch<CELL, 2>(nch, a, tiles, lds, s);
-    return launch_nch<CELL, 1>(nch, a, tiles, lds, s);
+    if (ms == 2) return launch_nch<CELL, 2>(nch, a, tiles, lds, lds_max, s);
+    return launch_nch<CELL, 1>(nch, a, tiles, lds, lds_max, s);
 }
 
 }  // namespace
@@ -508,9 +525,9 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
     a.H = H; a.C = C; a.N = N; a.Q_run = Q_run; a.d = lay.d; a.L = lay.L; a.R = lay.R;
     a.KG = lay.KG; a.nJB = lay.nJB; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
     switch (lay.cell) {
-        case ELM_CELL_ELMAN: return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, stream);
-        case ELM_CELL_LSTM:  return launch_cell<ELM_CELL_LSTM>(ms, nch, a, N, lds_per_row, stream);
-        case ELM_CELL_GRU:   return launch_cell<ELM_CELL_GRU>(ms, nch, a, N, lds_per_row, stream);
+        case ELM_CELL_ELMAN: return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
+        case ELM_CELL_LSTM:  return launch_cell<ELM_CELL_LSTM>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
+        case ELM_CELL_GRU:   return launch_cell<ELM_CELL_GRU>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
         default: return hipErrorInvalidValue;
     }
 }
