@@ -297,56 +297,58 @@ __global__ __launch_bounds__(kThreads) void stream_rows_kernel(const float* __re
     double rss = 0.0, h2 = 0.0;
     const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
     const int64_t nwaves = (int64_t)gridDim.x * 4;
-    // two rows per trip: both rows' loads are in flight before either is reduced
-    for (int64_t row0 = wave_id; row0 < N; row0 += 2 * nwaves) {
-        float hv[2][EPL];
+    // the next row of this wave is requested before the current one is reduced
+    float hn[EPL];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t row = row0 + u * nwaves;
+    for (int e = 0; e < EPL; ++e) {
+        const int jx = e * 64 + lane;
+        hn[e] = (wave_id < N && jx < L) ? H[wave_id * L + jx] : 0.0f;
+    }
+    for (int64_t row = wave_id; row < N; row += nwaves) {
+        float hv[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) hv[e] = hn[e];
+        const int64_t nxt = row + nwaves;
+        if (nxt < N) {
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
                 const int jx = e * 64 + lane;
-                hv[u][e] = (row < N && jx < L) ? H[row * L + jx] : 0.0f;
+                hn[e] = (jx < L) ? H[nxt * L + jx] : 0.0f;
             }
         }
+        double dot[M];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t row = row0 + u * nwaves;
-            if (row >= N) break;
-            double dot[M];
+        for (int c = 0; c < M; ++c) dot[c] = 0.0;
 #pragma unroll
-            for (int c = 0; c < M; ++c) dot[c] = 0.0;
+        for (int e = 0; e < EPL; ++e) {
+            const double h = (double)hv[e];
+            if (MODE == 0) h2 = fma(h, h, h2);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const double h = (double)hv[u][e];
-                if (MODE == 0) h2 = fma(h, h, h2);
+            for (int c = 0; c < M; ++c) dot[c] = fma(h, bt[e][c], dot[c]);
+        }
 #pragma unroll
-                for (int c = 0; c < M; ++c) dot[c] = fma(h, bt[e][c], dot[c]);
-            }
+        for (int c = 0; c < M; ++c) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) dot[c] += __shfl_xor(dot[c], off);
+        }
+        if (MODE == 0) {
+            double res[M];
 #pragma unroll
             for (int c = 0; c < M; ++c) {
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) dot[c] += __shfl_xor(dot[c], off);
+                res[c] = (c < m) ? (double)T[row * m + c] - dot[c] : 0.0;
+                if (lane == 0) rss = fma(res[c], res[c], rss);
             }
-            if (MODE == 0) {
-                double res[M];
 #pragma unroll
-                for (int c = 0; c < M; ++c) {
-                    res[c] = (c < m) ? (double)T[row * m + c] - dot[c] : 0.0;
-                    if (lane == 0) rss = fma(res[c], res[c], rss);
-                }
+            for (int e = 0; e < EPL; ++e) {
+                const double h = (double)hv[e];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    const double h = (double)hv[u][e];
-#pragma unroll
-                    for (int c = 0; c < M; ++c) gacc[e][c] = fma(h, res[c], gacc[e][c]);
-                }
-            } else if (lane < m) {
-                double v = dot[0];
-#pragma unroll
-                for (int c = 1; c < M; ++c) v = (lane == c) ? dot[c] : v;
-                Y[row * m + lane] = (float)v;
+                for (int c = 0; c < M; ++c) gacc[e][c] = fma(h, res[c], gacc[e][c]);
             }
+        } else if (lane < m) {
+            double v = dot[0];
+#pragma unroll
+            for (int c = 1; c < M; ++c) v = (lane == c) ? dot[c] : v;
+            Y[row * m + lane] = (float)v;
         }
     }
     if (MODE == 0) {
