@@ -27,9 +27,11 @@ import synthdata  # noqa: E402
 GATES = {"elman": 1, "lstm": 4, "gru": 3}
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
 
-# HBM traffic of one hidden-matrix kernel launch, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs scaled by a copy kernel of known size (profiles/ holds the summaries these come from).
-MEASURED_TRAFFIC_BYTES = {}
+# Memory traffic of one hidden-matrix kernel launch, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by a copy kernel of known size (profiles/ holds the summaries these come from).  The
+# counters sit at the L2 boundary: they include refills of the L2-resident weight operand from the
+# Infinity Cache, which never reach HBM.
+MEASURED_TRAFFIC_BYTES = {"cfg5": 922.8e9 + 39.1e9}   # profiles/hidden_kernel_cfg5_pmc.txt (L2-boundary traffic)
 
 
 def stage1_flops(cfg) -> float:

@@ -47,6 +47,19 @@ double frobenius(const std::vector<double>& a) {
     return std::sqrt(s);
 }
 
+// C = B * B for row-major n x n matrices (host).
+void square_into(const double* __restrict__ B, double* __restrict__ C, int n) {
+    for (int i = 0; i < n; ++i) {
+        double* crow = C + (size_t)i * n;
+        for (int j = 0; j < n; ++j) crow[j] = 0.0;
+        for (int k = 0; k < n; ++k) {
+            const double bik = B[(size_t)i * n + k];
+            const double* brow = B + (size_t)k * n;
+            for (int j = 0; j < n; ++j) crow[j] += bik * brow[j];
+        }
+    }
+}
+
 // Spectral radius by Gelfand's formula rho = lim ||A^k||^(1/k) along k = 2^i with renormalised
 // repeated squaring: A^(2^i) = exp(2^i s_i) B_i, ||B_i||_F = 1, s_{i+1} = s_i + 2^-(i+1) log||B_i^2||_F.
 double spectral_radius(const std::vector<double>& A, int n) {
@@ -57,14 +70,7 @@ double spectral_radius(const std::vector<double>& A, int n) {
     double log_rho = std::log(nf), w = 1.0, prev = -1.0;
     int settled = 0;
     for (int it = 0; it < 48; ++it) {       // 2^-48 * |log ||B^2||| is below double rounding of log rho
-        std::fill(C.begin(), C.end(), 0.0);
-        for (int i = 0; i < n; ++i)
-            for (int k = 0; k < n; ++k) {
-                const double bik = B[(size_t)i * n + k];
-                const double* brow = &B[(size_t)k * n];
-                double* crow = &C[(size_t)i * n];
-                for (int j = 0; j < n; ++j) crow[j] += bik * brow[j];
-            }
+        square_into(B.data(), C.data(), n);
         const double nc = frobenius(C);
         if (nc == 0.0) return 0.0;       // nilpotent
         w *= 0.5;
