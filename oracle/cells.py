@@ -91,7 +91,35 @@ def hidden_gru(X, W, U, b, h0=None, steps=None):
     return h
 
 
-GATES = {"elman": 1, "lstm": 4, "gru": 3}
+def hidden_elman_diag(X, W, alpha, b, steps=None):
+    """The paper's own Elman cell (section "Elman", Eq. hij_elman): every neuron feeds back only on
+    itself, from all earlier steps of the window.
+
+    h_j(t) = tanh( x(t) W[:, j] + b_j + sum_{k=1}^{t-1} alpha[j, k-1] h_j(t-k) ),  t = 1..steps,
+    with alpha of shape [L, Q] (column k-1 holds the weight of lag k) and no state before t = 1.
+    The printed equation and Algorithm "Basic-PR-ELM" omit the activation, index the bias by sample
+    and let the lag loop include step t itself; this is the reading with g applied, a bias per
+    neuron and strictly earlier steps only.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    alpha = np.asarray(alpha, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    N, Q, d = X.shape
+    L = W.shape[1]
+    steps = Q if steps is None else int(steps)
+    if not 0 <= steps <= Q or alpha.shape != (L, Q):
+        raise ValueError("alpha must be [L, Q] and steps must lie in [0, Q]")
+    hist = np.zeros((steps + 1, N, L))           # hist[t] = h(t), hist[0] unused (no state before t = 1)
+    for t in range(1, steps + 1):
+        a = X[:, t - 1, :] @ W + b
+        for k in range(1, t):
+            a = a + alpha[:, k - 1] * hist[t - k]
+        hist[t] = np.tanh(a)
+    return hist[steps] if steps > 0 else np.zeros((N, L))
+
+
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
 
 
 def hidden(cell: str, X, W, U, b, h0=None, c0=None, steps=None):
@@ -102,6 +130,10 @@ def hidden(cell: str, X, W, U, b, h0=None, c0=None, steps=None):
         return hidden_lstm(X, W, U, b, h0=h0, c0=c0, steps=steps)
     if cell == "gru":
         return hidden_gru(X, W, U, b, h0=h0, steps=steps)
+    if cell == "elman_diag":
+        if h0 is not None:
+            raise ValueError("the multi-lag cell has no single initial state")
+        return hidden_elman_diag(X, W, U, b, steps=steps)
     raise ValueError(f"unknown cell {cell!r}")
 
 

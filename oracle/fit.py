@@ -21,7 +21,7 @@ def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0,
     if T.ndim == 1:
         T = T[:, None]
     N, Q, d = X.shape
-    W, U, b = weights.draw(cell, d, L, seed, w_scale, spectral_radius, forget_bias, zero_bias)
+    W, U, b = weights.draw(cell, d, L, seed, w_scale, spectral_radius, forget_bias, zero_bias, Q=Q)
     H = cells.hidden_chunked(cell, X, W, U, b, chunk=chunk)
     if N <= chunk:
         beta, rss, R = lstsq.solve(H, T)

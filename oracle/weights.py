@@ -19,7 +19,7 @@ from __future__ import annotations
 
 import numpy as np
 
-GATES = {"elman": 1, "lstm": 4, "gru": 3}
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
 
 _GAMMA = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
@@ -47,15 +47,22 @@ def spectral_radius(U: np.ndarray) -> float:
 
 def draw(cell: str, d: int, L: int, seed: int, w_scale: float = 1.0,
          spectral_radius_target: float = 0.0, forget_bias: float = 0.0,
-         zero_bias: bool = False):
-    """Return (W [d,kL], U [L,kL], b [kL]) as float32 arrays."""
+         zero_bias: bool = False, Q: int = 0):
+    """Return (W [d,kL], U [L,kL], b [kL]) as float32 arrays.
+
+    For the paper's own Elman cell ("elman_diag") the recurrent weights are alpha [L, Q] (lag k in
+    column k-1), drawn in the same place of the stream as U.
+    """
     k = GATES[cell]
     kL = k * L
-    n = d * kL + L * kL + kL
+    ucols = Q if cell == "elman_diag" else kL
+    if cell == "elman_diag" and Q < 1:
+        raise ValueError("the multi-lag cell needs Q")
+    n = d * kL + L * ucols + kL
     v = (2.0 * uniform01(seed, n) - 1.0) * float(w_scale)
     W = v[:d * kL].reshape(d, kL)
-    U = v[d * kL:d * kL + L * kL].reshape(L, kL)
-    b = v[d * kL + L * kL:].copy()
+    U = v[d * kL:d * kL + L * ucols].reshape(L, ucols)
+    b = v[d * kL + L * ucols:].copy()
     if spectral_radius_target > 0.0:
         if cell != "elman":
             raise ValueError("spectral-radius scaling is defined for the Elman cell only")

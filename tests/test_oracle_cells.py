@@ -254,3 +254,59 @@ def test_rows_are_independent_and_chunking_is_exact(cell, k):
     np.testing.assert_allclose(cells.hidden_chunked(cell, X, W, U, b, chunk=8), full, atol=1e-15)
     one = cells.hidden(cell, X[11:12], W, U, b)
     np.testing.assert_allclose(one[0], full[11], atol=1e-15)
+
+
+# ----------------------------------------------------------------- the paper's own (diagonal, multi-lag) Elman
+
+def test_elman_diag_without_feedback_is_feedforward_elm():
+    N, Q, d, L = 5, 4, 3, 6
+    X, W, b = rnd((N, Q, d), 70), rnd((d, L), 71), rnd(L, 72)
+    H = cells.hidden_elman_diag(X, W, np.zeros((L, Q)), b)
+    np.testing.assert_allclose(H, np.tanh(X[:, Q - 1, :] @ W + b), atol=1e-15)
+    H1 = cells.hidden_elman_diag(X[:, :1], W, rnd((L, 1), 73), b)     # Q = 1: no earlier step exists
+    np.testing.assert_allclose(H1, np.tanh(X[:, 0, :] @ W + b), atol=1e-15)
+
+
+def test_elman_diag_lag_one_only_equals_the_dense_cell_with_a_diagonal_matrix():
+    N, Q, d, L = 6, 7, 2, 5
+    X, W, b = rnd((N, Q, d), 74), rnd((d, L), 75), rnd(L, 76)
+    u = rnd(L, 77)
+    alpha = np.zeros((L, Q))
+    alpha[:, 0] = u
+    np.testing.assert_allclose(cells.hidden_elman_diag(X, W, alpha, b),
+                               cells.hidden_elman(X, W, np.diag(u), b), atol=1e-15)
+
+
+def test_elman_diag_scalar_iteration_by_hand():
+    # one neuron, three steps: h1 = g(w x1 + b); h2 = g(w x2 + b + a1 h1); h3 = g(w x3 + b + a1 h2 + a2 h1)
+    w, b, a1, a2, a3 = 0.6, -0.1, 0.5, -0.7, 0.9
+    x = [0.2, -0.4, 0.8]
+    h1 = math.tanh(w * x[0] + b)
+    h2 = math.tanh(w * x[1] + b + a1 * h1)
+    h3 = math.tanh(w * x[2] + b + a1 * h2 + a2 * h1)
+    H = cells.hidden_elman_diag(np.array(x).reshape(1, 3, 1), [[w]], [[a1, a2, a3]], [b])
+    assert abs(H[0, 0] - h3) < 1e-15
+    H2 = cells.hidden_elman_diag(np.array(x).reshape(1, 3, 1), [[w]], [[a1, a2, a3]], [b], steps=2)
+    assert abs(H2[0, 0] - h2) < 1e-15
+
+
+def test_elman_diag_brute_force_from_the_equation():
+    N, Q, d, L = 3, 5, 2, 4
+    X, W, alpha, b = rnd((N, Q, d), 78), rnd((d, L), 79), rnd((L, Q), 80), rnd(L, 81)
+    ref = np.zeros((N, L))
+    for i in range(N):
+        for j in range(L):
+            h = {}
+            for t in range(1, Q + 1):
+                a = sum(W[s][j] * X[i, t - 1, s] for s in range(d)) + b[j]
+                a += sum(alpha[j][k - 1] * h[t - k] for k in range(1, t))
+                h[t] = math.tanh(a)
+            ref[i, j] = h[Q]
+    got = cells.hidden_elman_diag(X, W, alpha, b)
+    np.testing.assert_allclose(got, ref, atol=1e-14)
+    # neurons do not interact: changing one neuron's alpha row changes only that column
+    alpha2 = alpha.copy()
+    alpha2[2] += 0.3
+    got2 = cells.hidden_elman_diag(X, W, alpha2, b)
+    assert np.abs(got2[:, 2] - got[:, 2]).max() > 1e-3
+    np.testing.assert_array_equal(np.delete(got2, 2, axis=1), np.delete(got, 2, axis=1))
