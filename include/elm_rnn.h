@@ -28,7 +28,8 @@
  *     axis so that one step of one sample is contiguous.
  *   - Weight layout: W is d x kL, U is L x kL, b is kL with k gate blocks side
  *     by side: Elman k = 1; LSTM k = 4 in the order (i, f, o, g) = the paper's
- *     (in, lambda, o, candidate); GRU k = 3 in the order (z, r, n).
+ *     (in, lambda, o, candidate); GRU k = 3 in the order (z, r, n).  For
+ *     ELM_CELL_ELMAN_DIAG k = 1 and U is the L x Q lag-weight matrix alpha.
  *   - Supported sizes: 1 <= L <= 512, 1 <= d <= 64, 1 <= m <= 16, N >= 1.
  */
 #ifndef ELM_RNN_H
@@ -45,6 +46,12 @@ extern "C" {
                               "Fully Connected RNN" / "Elman" recurrences                        */
 #define ELM_CELL_LSTM  1   /* the paper's section "LSTM" (no peepholes)                          */
 #define ELM_CELL_GRU   2   /* the paper's section "GRU": f = (1-z) f_prev + z tanh(W x + U (r f_prev) + b) */
+
+#define ELM_CELL_ELMAN_DIAG 3 /* the paper's section "Elman" as printed (Eq. hij_elman): neuron j feeds
+                                back on itself only, from every earlier step of the window:
+                                h_j(t) = tanh(x(t) W[:,j] + b_j + sum_{k=1}^{t-1} alpha[j][k-1] h_j(t-k));
+                                its recurrent array "U" is alpha, L x Q (lag k in column k-1), Q <= 512;
+                                no initial state can be passed and Q_run <= Q                        */
 
 #define ELM_OK            0
 #define ELM_EINVAL       -1   /* null pointer, non-positive size, unknown cell, N < L for a solve */
@@ -91,7 +98,8 @@ typedef struct {
 int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
                          const elm_rnn_init* init, elm_rnn_model** model_out);
 
-/* Same, but with caller-supplied float32 host weights W[d*kL], U[L*kL], b[kL] (copied). */
+/* Same, but with caller-supplied float32 host weights W[d*kL], U[L*kL] (alpha[L*Q] for
+ * ELM_CELL_ELMAN_DIAG), b[kL] (copied). */
 int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m,
                                       const float* W, const float* U, const float* b,
                                       elm_rnn_model** model_out);

@@ -8,8 +8,8 @@ from typing import Optional
 
 import numpy as np
 
-CELLS = {"elman": 0, "lstm": 1, "gru": 2}
-GATES = {"elman": 1, "lstm": 4, "gru": 3}
+CELLS = {"elman": 0, "lstm": 1, "gru": 2, "elman_diag": 3}
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
 
 ELM_OK, ELM_EINVAL, ELM_EWORKSPACE, ELM_ERANK, ELM_EHIP, ELM_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
@@ -156,14 +156,16 @@ class Model:
 
     @classmethod
     def from_weights(cls, cell: str, Q: int, m: int, W, U, b) -> "Model":
-        """elm_rnn_model_create_from_weights with host float32 arrays W [d,kL], U [L,kL], b [kL]."""
+        """elm_rnn_model_create_from_weights with host float32 arrays W [d,kL], U [L,kL], b [kL]
+        (for "elman_diag" U is the lag-weight matrix alpha [L, Q])."""
         lib = load_library()
         W = np.ascontiguousarray(W, dtype=np.float32)
         U = np.ascontiguousarray(U, dtype=np.float32)
         b = np.ascontiguousarray(b, dtype=np.float32)
         k = GATES[cell]
         L, d = U.shape[0], W.shape[0]
-        if U.shape != (L, k * L) or W.shape != (d, k * L) or b.shape != (k * L,):
+        ucols = Q if cell == "elman_diag" else k * L
+        if U.shape != (L, ucols) or W.shape != (d, k * L) or b.shape != (k * L,):
             raise ValueError("weight shapes do not match the cell")
         out = C.c_void_p()
         _check(lib.elm_rnn_model_create_from_weights(CELLS[cell], Q, d, L, m, W.ctypes.data, U.ctypes.data,
@@ -175,7 +177,7 @@ class Model:
         lib = load_library()
         k = GATES[self.cell]
         W = np.empty((self.d, k * self.L), np.float32)
-        U = np.empty((self.L, k * self.L), np.float32)
+        U = np.empty((self.L, self.Q if self.cell == "elman_diag" else k * self.L), np.float32)
         b = np.empty(k * self.L, np.float32)
         beta = np.empty((self.L, self.m), np.float64)
         _check(lib.elm_rnn_get_weights(self._h, W.ctypes.data, U.ctypes.data, b.ctypes.data, beta.ctypes.data))

@@ -1,6 +1,7 @@
 // C ABI of libelmrnn: argument checks, the seeded weight generator (step 1 of the paper's
 // Algorithm "S-R-ELM"), model life-cycle and the orchestration of stage 1 and stage 2.
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -13,7 +14,8 @@ struct elm_rnn_model {
     int cell, Q, d, L, m, G;
     elm::PackedLayout lay;
     std::vector<float> W, U, b;   // host copies, float32
-    float* dWp = nullptr;         // packed [U; W; b] on the device
+    float* dWp = nullptr;         // packed [U; W; b] on the device (dense cells)
+    float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
     double* dBeta = nullptr;      // L x m float64 on the device
 };
 
@@ -90,10 +92,18 @@ double spectral_radius(const std::vector<double>& A, int n) {
 }
 
 int check_dims(int cell, int Q, int d, int L, int m) {
-    if (cell != ELM_CELL_ELMAN && cell != ELM_CELL_LSTM && cell != ELM_CELL_GRU) return ELM_EINVAL;
+    if (cell != ELM_CELL_ELMAN && cell != ELM_CELL_LSTM && cell != ELM_CELL_GRU &&
+        cell != ELM_CELL_ELMAN_DIAG)
+        return ELM_EINVAL;
     if (Q < 1 || d < 1 || L < 1 || m < 1) return ELM_EINVAL;
     if (L > 512 || d > 64 || m > 16) return ELM_EUNSUPPORTED;
+    if (cell == ELM_CELL_ELMAN_DIAG && Q > kDiagMaxQ) return ELM_EUNSUPPORTED;
     return ELM_OK;
+}
+
+// columns of the recurrent weight array: k*L for the dense cells, Q lags for the diagonal cell
+size_t recurrent_cols(int cell, int Q, int L) {
+    return cell == ELM_CELL_ELMAN_DIAG ? (size_t)Q : (size_t)gates_of(cell) * L;
 }
 
 int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, std::vector<float>&& U,
@@ -101,14 +111,26 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
     elm_rnn_model* mdl = new (std::nothrow) elm_rnn_model();
     if (mdl == nullptr) return ELM_EINVAL;
     mdl->cell = cell; mdl->Q = Q; mdl->d = d; mdl->L = L; mdl->m = m; mdl->G = gates_of(cell);
-    mdl->lay = packed_layout(cell, d, L);
     mdl->W = std::move(W); mdl->U = std::move(U); mdl->b = std::move(b);
-    std::vector<float> packed(mdl->lay.floats);
-    pack_weights(mdl->lay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
-    hipError_t e = hipMalloc(&mdl->dWp, packed.size() * sizeof(float));
+    std::vector<float> packed;
+    float** dst = &mdl->dWp;
+    if (cell == ELM_CELL_ELMAN_DIAG) {
+        mdl->lay = PackedLayout{};
+        packed.resize((size_t)L * d + (size_t)L * Q + L);
+        for (int j = 0; j < L; ++j)
+            for (int s = 0; s < d; ++s) packed[(size_t)j * d + s] = mdl->W[(size_t)s * L + j];
+        std::copy(mdl->U.begin(), mdl->U.end(), packed.begin() + (size_t)L * d);
+        std::copy(mdl->b.begin(), mdl->b.end(), packed.begin() + (size_t)L * d + (size_t)L * Q);
+        dst = &mdl->dDiag;
+    } else {
+        mdl->lay = packed_layout(cell, d, L);
+        packed.resize(mdl->lay.floats);
+        pack_weights(mdl->lay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
+    }
+    hipError_t e = hipMalloc(dst, packed.size() * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
-        e = hipMemcpy(mdl->dWp, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
+        e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(mdl->dBeta, 0, (size_t)L * m * sizeof(double));
     if (e != hipSuccess) {
         set_hip_error(e, "model upload");
@@ -117,6 +139,19 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
     }
     *out = mdl;
     return ELM_OK;
+}
+
+// stage 1 for any cell
+hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N,
+                      int Q_run, const float* h0, const float* c0, float* H, float* C, hipStream_t stream) {
+    if (mdl->cell == ELM_CELL_ELMAN_DIAG) {
+        const float* Wt = mdl->dDiag;
+        const float* alpha = Wt + (size_t)mdl->L * mdl->d;
+        const float* bias = alpha + (size_t)mdl->L * mdl->Q;
+        return launch_hidden_diag(Wt, alpha, bias, mdl->Q, X, ldx_n, ldx_q, N, Q_run, mdl->d, mdl->L, H,
+                                  stream);
+    }
+    return launch_hidden(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
 }
 
 struct EventPair {
@@ -195,7 +230,7 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
     if (init->spectral_radius > 0.0 && cell != ELM_CELL_ELMAN) return ELM_EINVAL;
     const int G = gates_of(cell), GL = G * L;
     SplitMix64 rng(seed);
-    std::vector<double> W((size_t)d * GL), U((size_t)L * GL), b((size_t)GL);
+    std::vector<double> W((size_t)d * GL), U((size_t)L * recurrent_cols(cell, Q, L)), b((size_t)GL);
     for (double& v : W) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
     for (double& v : U) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
     for (double& v : b) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
@@ -220,7 +255,8 @@ int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m, cons
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
     const size_t GL = (size_t)gates_of(cell) * L;
-    std::vector<float> Wf(W, W + (size_t)d * GL), Uf(U, U + (size_t)L * GL), bf(b, b + GL);
+    std::vector<float> Wf(W, W + (size_t)d * GL), Uf(U, U + (size_t)L * recurrent_cols(cell, Q, L)),
+        bf(b, b + GL);
     return build_model(cell, Q, d, L, m, std::move(Wf), std::move(Uf), std::move(bf), model_out);
 }
 
@@ -245,6 +281,7 @@ int elm_rnn_set_beta(elm_rnn_model* model, const double* beta64) {
 void elm_rnn_free(elm_rnn_model* model) {
     if (model == nullptr) return;
     if (model->dWp) (void)hipFree(model->dWp);
+    if (model->dDiag) (void)hipFree(model->dDiag);
     if (model->dBeta) (void)hipFree(model->dBeta);
     delete model;
 }
@@ -254,8 +291,11 @@ int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, in
                    float* c_out, void* hip_stream) {
     if (model == nullptr || X == nullptr || H_out == nullptr) return ELM_EINVAL;
     if (N < 1 || Q_run < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
-    ELM_HIP_TRY(launch_hidden(model->lay, model->dWp, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out,
-                              static_cast<hipStream_t>(hip_stream)));
+    if (model->cell == ELM_CELL_ELMAN_DIAG && (h0 != nullptr || c0 != nullptr || c_out != nullptr ||
+                                               Q_run > model->Q))
+        return ELM_EINVAL;
+    ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out,
+                           static_cast<hipStream_t>(hip_stream)));
     return ELM_OK;
 }
 
@@ -300,7 +340,7 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
     hipError_t e = ev.create();
     if (e == hipSuccess) e = hipEventRecord(ev.a, stream);
     if (e == hipSuccess)
-        e = launch_hidden(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q, nullptr, nullptr, H, nullptr, stream);
+        e = run_hidden(mdl, X, ldx_n, ldx_q, N, Q, nullptr, nullptr, H, nullptr, stream);
     if (e == hipSuccess) e = hipEventRecord(ev.b, stream);
     if (e != hipSuccess) {
         set_hip_error(e, "hidden-matrix stage");
@@ -348,8 +388,7 @@ int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, i
         return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float* H = static_cast<float*>(workspace);
-    ELM_HIP_TRY(launch_hidden(model->lay, model->dWp, X, ldx_n, ldx_q, N, model->Q, nullptr, nullptr, H,
-                              nullptr, stream));
+    ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, model->Q, nullptr, nullptr, H, nullptr, stream));
     ELM_HIP_TRY(launch_predict_gemv(H, model->dBeta, N, model->L, model->m, Y_out, stream));
     return ELM_OK;
 }

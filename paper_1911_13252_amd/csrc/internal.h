@@ -20,7 +20,7 @@ struct PackedLayout {
     size_t floats;   // packed buffer length including the prefetch tail
 };
 
-inline int gates_of(int cell) { return cell == ELM_CELL_ELMAN ? 1 : cell == ELM_CELL_LSTM ? 4 : 3; }
+inline int gates_of(int cell) { return cell == ELM_CELL_LSTM ? 4 : cell == ELM_CELL_GRU ? 3 : 1; }
 PackedLayout packed_layout(int cell, int d, int L);
 
 // Pack host W (d x GL), U (L x GL), b (GL) into the kernel's fragment order.
@@ -29,6 +29,13 @@ void pack_weights(const PackedLayout& lay, const float* W, const float* U, const
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
                          float* H, float* C, hipStream_t stream);
+
+// The paper's own Elman cell (diagonal, multi-lag feedback).  Wt is W transposed [L][d], alpha is
+// [L][lda] with lag k in column k-1, Q <= lda steps are run.
+constexpr int kDiagMaxQ = 512;
+hipError_t launch_hidden_diag(const float* Wt, const float* alpha, const float* bias, int lda,
+                              const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
+                              float* H, hipStream_t stream);
 
 // ---- stage 2 -------------------------------------------------------------------------------
 struct SolvePlan {
