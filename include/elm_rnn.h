@@ -53,6 +53,18 @@ extern "C" {
                                 its recurrent array "U" is alpha, L x Q (lag k in column k-1), Q <= 512;
                                 no initial state can be passed and Q_run <= Q                        */
 
+/* How the dense cells carry the recurrent contraction h_{t-1} U of each step (the input part x_t W + b
+ * and all point-wise work are float32-exact in both):
+ *   ELM_CONTRACT_FP32    float32 matrix instructions (the default);
+ *   ELM_CONTRACT_SPLIT16 every float32 operand value is split into an fp16 pair hi + lo (22 significant
+ *                        bits) and the product is taken as hi*hi + hi*lo + lo*hi on fp16 matrix
+ *                        instructions with float32 accumulation: float32-equivalent results (the
+ *                        dropped term is 2^-22 relative) at several times the throughput.  Needs
+ *                        d <= 15 and finite weights; |h0| must stay below 8 (states produced by the
+ *                        cells lie in [-1, 1]). */
+#define ELM_CONTRACT_FP32    0
+#define ELM_CONTRACT_SPLIT16 1
+
 #define ELM_OK            0
 #define ELM_EINVAL       -1   /* null pointer, non-positive size, unknown cell, N < L for a solve */
 #define ELM_EWORKSPACE   -2   /* workspace pointer null or smaller than the *_workspace_bytes()   */
@@ -75,6 +87,7 @@ typedef struct {
     double spectral_radius;
     double forget_bias;
     int    zero_bias;
+    int    contraction;   /* ELM_CONTRACT_*: how models made from this init run the recurrence */
 } elm_rnn_init;
 
 /* Filled by elm_rnn_solve / elm_rnn_fit (host memory). */
@@ -103,6 +116,10 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
 int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m,
                                       const float* W, const float* U, const float* b,
                                       elm_rnn_model** model_out);
+
+/* Switch an existing model between the contraction modes (ELM_CONTRACT_*).  Returns
+ * ELM_EUNSUPPORTED, leaving the model unchanged, if it cannot run the requested mode. */
+int elm_rnn_model_set_contraction(elm_rnn_model* model, int contraction);
 
 /* Copy the model's weights to host arrays (any of W, U, b, beta64 may be NULL).  beta64 is the
  * L x m float64 output-weight matrix.  Synchronous. */

@@ -15,7 +15,7 @@ ELM_OK, ELM_EINVAL, ELM_EWORKSPACE, ELM_ERANK, ELM_EHIP, ELM_EUNSUPPORTED = 0, -
 
 DECLARED_SYMBOLS = (
     "elm_rnn_model_create", "elm_rnn_model_create_from_weights", "elm_rnn_get_weights",
-    "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
+    "elm_rnn_model_set_contraction", "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
     "elm_rnn_solve", "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
     "elm_rnn_predict_workspace_bytes", "elm_rnn_predict", "elm_rnn_strerror",
     "elm_rnn_last_hip_error",
@@ -30,7 +30,7 @@ class ElmRnnError(RuntimeError):
 
 class _Init(C.Structure):
     _fields_ = [("w_scale", C.c_double), ("spectral_radius", C.c_double),
-                ("forget_bias", C.c_double), ("zero_bias", C.c_int)]
+                ("forget_bias", C.c_double), ("zero_bias", C.c_int), ("contraction", C.c_int)]
 
 
 class _Stats(C.Structure):
@@ -78,6 +78,7 @@ def load_library():
     lib.elm_rnn_model_create_from_weights.argtypes = [C.c_int] * 5 + [vp, vp, vp, C.POINTER(vp)]
     lib.elm_rnn_get_weights.argtypes = [vp, vp, vp, vp, vp]
     lib.elm_rnn_set_beta.argtypes = [vp, vp]
+    lib.elm_rnn_model_set_contraction.argtypes = [vp, C.c_int]
     lib.elm_rnn_free.argtypes = [vp]
     lib.elm_rnn_free.restype = None
     lib.elm_rnn_hidden.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp]
@@ -128,8 +129,12 @@ def _x_strides(X):
     return int(X.stride(0)), int(X.stride(1))
 
 
-def _init_struct(w_scale, spectral_radius, forget_bias, zero_bias) -> _Init:
-    return _Init(float(w_scale), float(spectral_radius), float(forget_bias), int(bool(zero_bias)))
+CONTRACTIONS = {"fp32": 0, "split16": 1}
+
+
+def _init_struct(w_scale, spectral_radius, forget_bias, zero_bias, contraction="fp32") -> _Init:
+    return _Init(float(w_scale), float(spectral_radius), float(forget_bias), int(bool(zero_bias)),
+                 CONTRACTIONS[contraction])
 
 
 def _stats(s: _Stats, rank_deficient: bool) -> Stats:
@@ -146,11 +151,11 @@ class Model:
 
     @classmethod
     def create(cls, cell: str, Q: int, d: int, L: int, m: int, seed: int, *, w_scale=1.0,
-               spectral_radius=0.0, forget_bias=0.0, zero_bias=False) -> "Model":
+               spectral_radius=0.0, forget_bias=0.0, zero_bias=False, contraction="fp32") -> "Model":
         """elm_rnn_model_create: weights drawn from the seed on the host, uploaded."""
         lib = load_library()
         out = C.c_void_p()
-        init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias)
+        init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias, contraction)
         _check(lib.elm_rnn_model_create(CELLS[cell], Q, d, L, m, C.c_uint64(seed), C.byref(init), C.byref(out)))
         return cls(out.value, cell, Q, d, L, m)
 
@@ -182,6 +187,10 @@ class Model:
         beta = np.empty((self.L, self.m), np.float64)
         _check(lib.elm_rnn_get_weights(self._h, W.ctypes.data, U.ctypes.data, b.ctypes.data, beta.ctypes.data))
         return W, U, b, beta
+
+    def set_contraction(self, contraction: str) -> None:
+        """elm_rnn_model_set_contraction: "fp32" or "split16"."""
+        _check(load_library().elm_rnn_model_set_contraction(self._h, CONTRACTIONS[contraction]))
 
     def set_beta(self, beta64) -> None:
         lib = load_library()
@@ -270,7 +279,7 @@ class FitResult:
 
 
 def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0, forget_bias=0.0,
-        zero_bias=False, keep_H: bool = True, workspace=None, H_out=None, stream=None,
+        zero_bias=False, contraction="fp32", keep_H: bool = True, workspace=None, H_out=None, stream=None,
         allow_rank_deficient: bool = False) -> FitResult:
     """elm_rnn_fit: Algorithm "S-R-ELM" end to end on device tensors X [N,Q,d], T [N,m]."""
     import torch
@@ -294,7 +303,7 @@ def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0,
     beta64 = torch.empty((L, m), dtype=torch.float64, device=X.device)
     st = _Stats()
     out = C.c_void_p()
-    init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias)
+    init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias, contraction)
     rc = lib.elm_rnn_fit(CELLS[cell], X.data_ptr(), ldn, ldq, T.data_ptr(), N, Q, d, L, m, C.c_uint64(seed),
                          C.byref(init), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream),
                          None if H is None else H.data_ptr(), beta32.data_ptr(), beta64.data_ptr(),

@@ -16,6 +16,9 @@ struct elm_rnn_model {
     std::vector<float> W, U, b;   // host copies, float32
     float* dWp = nullptr;         // packed [U; W; b] on the device (dense cells)
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
+    int contraction = ELM_CONTRACT_FP32;
+    elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
+    void* dWs = nullptr;
     double* dBeta = nullptr;      // L x m float64 on the device
 };
 
@@ -141,6 +144,20 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
     return ELM_OK;
 }
 
+// Build and upload the split-format weights of a model (once); ELM_EUNSUPPORTED if the model
+// cannot use the mode.
+int enable_split(elm_rnn_model* mdl) {
+    if (mdl->dWs != nullptr) return ELM_OK;
+    if (mdl->cell == ELM_CELL_ELMAN_DIAG) return ELM_EUNSUPPORTED;
+    mdl->slay = split_layout(mdl->cell, mdl->d, mdl->L, mdl->W.data(), mdl->U.data(), mdl->b.data());
+    if (!mdl->slay.ok) return ELM_EUNSUPPORTED;
+    std::vector<unsigned char> packed(mdl->slay.bytes);
+    pack_weights_split(mdl->slay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
+    ELM_HIP_TRY(hipMalloc(&mdl->dWs, packed.size()));
+    ELM_HIP_TRY(hipMemcpy(mdl->dWs, packed.data(), packed.size(), hipMemcpyHostToDevice));
+    return ELM_OK;
+}
+
 // stage 1 for any cell
 hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N,
                       int Q_run, const float* h0, const float* c0, float* H, float* C, hipStream_t stream) {
@@ -151,6 +168,8 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
         return launch_hidden_diag(Wt, alpha, bias, mdl->Q, X, ldx_n, ldx_q, N, Q_run, mdl->d, mdl->L, H,
                                   stream);
     }
+    if (mdl->contraction == ELM_CONTRACT_SPLIT16 && mdl->dWs != nullptr)
+        return launch_hidden_split(mdl->slay, mdl->dWs, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     return launch_hidden(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
 }
 
@@ -228,6 +247,7 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
     if (rc != ELM_OK) return rc;
     if (!(init->w_scale > 0.0) || init->spectral_radius < 0.0) return ELM_EINVAL;
     if (init->spectral_radius > 0.0 && cell != ELM_CELL_ELMAN) return ELM_EINVAL;
+    if (init->contraction != ELM_CONTRACT_FP32 && init->contraction != ELM_CONTRACT_SPLIT16) return ELM_EINVAL;
     const int G = gates_of(cell), GL = G * L;
     SplitMix64 rng(seed);
     std::vector<double> W((size_t)d * GL), U((size_t)L * recurrent_cols(cell, Q, L)), b((size_t)GL);
@@ -246,7 +266,15 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
         for (int j = 0; j < L; ++j) b[(size_t)L + j] += init->forget_bias;
     }
     std::vector<float> Wf(W.begin(), W.end()), Uf(U.begin(), U.end()), bf(b.begin(), b.end());
-    return build_model(cell, Q, d, L, m, std::move(Wf), std::move(Uf), std::move(bf), model_out);
+    rc = build_model(cell, Q, d, L, m, std::move(Wf), std::move(Uf), std::move(bf), model_out);
+    if (rc == ELM_OK && init->contraction != ELM_CONTRACT_FP32) {
+        rc = elm_rnn_model_set_contraction(*model_out, init->contraction);
+        if (rc != ELM_OK) {
+            elm_rnn_free(*model_out);
+            *model_out = nullptr;
+        }
+    }
+    return rc;
 }
 
 int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m, const float* W,
@@ -271,6 +299,18 @@ int elm_rnn_get_weights(const elm_rnn_model* model, float* W, float* U, float* b
     return ELM_OK;
 }
 
+int elm_rnn_model_set_contraction(elm_rnn_model* model, int contraction) {
+    if (model == nullptr) return ELM_EINVAL;
+    if (contraction == ELM_CONTRACT_FP32) {
+        model->contraction = contraction;
+        return ELM_OK;
+    }
+    if (contraction != ELM_CONTRACT_SPLIT16) return ELM_EINVAL;
+    const int rc = enable_split(model);
+    if (rc == ELM_OK) model->contraction = contraction;
+    return rc;
+}
+
 int elm_rnn_set_beta(elm_rnn_model* model, const double* beta64) {
     if (model == nullptr || beta64 == nullptr) return ELM_EINVAL;
     ELM_HIP_TRY(hipMemcpy(model->dBeta, beta64, (size_t)model->L * model->m * sizeof(double),
@@ -282,6 +322,7 @@ void elm_rnn_free(elm_rnn_model* model) {
     if (model == nullptr) return;
     if (model->dWp) (void)hipFree(model->dWp);
     if (model->dDiag) (void)hipFree(model->dDiag);
+    if (model->dWs) (void)hipFree(model->dWs);
     if (model->dBeta) (void)hipFree(model->dBeta);
     delete model;
 }

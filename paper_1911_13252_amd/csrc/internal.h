@@ -30,6 +30,25 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
                          float* H, float* C, hipStream_t stream);
 
+// ---- fast contraction mode (fp16 hi/lo split of the recurrent part, bf16 x 3 split of the input part)
+struct SplitLayout {
+    int cell, d, L, G;
+    int KGh;        // recurrent groups of 16 rows (ceil(L / 16))
+    int KGs;        // stream positions per column block: 2 for the input group + KGh
+    int nJB;        // hidden-unit blocks of 32 columns
+    int stride;     // LDS operand row stride in bytes
+    int xoff;       // byte offset of the input group inside an operand row
+    int log2_su;    // recurrent weights are scaled by 2^log2_su before the fp16 split
+    float inv_scale;   // 1 / (2^13 * 2^log2_su): accumulator -> pre-activation
+    size_t bytes;   // packed buffer length including the prefetch tail
+    bool ok;        // false: this model cannot use the mode (d > 15, non-finite or out-of-range weights)
+};
+SplitLayout split_layout(int cell, int d, int L, const float* W, const float* U, const float* b);
+void pack_weights_split(const SplitLayout& lay, const float* W, const float* U, const float* b, void* out);
+hipError_t launch_hidden_split(const SplitLayout& lay, const void* Wp, const float* X, int64_t ldx_n,
+                               int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
+                               float* H, float* C, hipStream_t stream);
+
 // The paper's own Elman cell (diagonal, multi-lag feedback).  Wt is W transposed [L][d], alpha is
 // [L][lda] with lag k in column k-1, Q <= lda steps are run.
 constexpr int kDiagMaxQ = 512;

@@ -47,20 +47,26 @@ SHAPES = [  # N, Q, d, L  (several tiles, ragged tails, every chunk count, awkwa
 ]
 
 
+MODES = ["fp32", "split16"]     # how the recurrent contraction is carried (same tolerance for both)
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
 @pytest.mark.parametrize("N,Q,d,L", SHAPES)
-def test_hidden_matches_oracle_small(elm, cell, N, Q, d, L):
+def test_hidden_matches_oracle_small(elm, cell, N, Q, d, L, mode):
     W, U, b = rand_weights(cell, d, L, seed=N + 7 * L)
     X = np.random.default_rng(N + L + Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    model.set_contraction(mode)
     H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
     ref = ocells.hidden(cell, X, W, U, b)
     assert_h_close(H, ref)
     model.close()
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
-def test_initial_state_truncation_and_cell_output(elm, cell):
+def test_initial_state_truncation_and_cell_output(elm, cell, mode):
     N, Q, d, L = 150, 6, 3, 70
     W, U, b = rand_weights(cell, d, L, seed=5)
     rng = np.random.default_rng(6)
@@ -68,6 +74,7 @@ def test_initial_state_truncation_and_cell_output(elm, cell):
     h0 = rng.uniform(-0.9, 0.9, (N, L)).astype(np.float32)
     c0 = rng.uniform(-2, 2, (N, L)).astype(np.float32)
     model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    model.set_contraction(mode)
     Xd, h0d, c0d = (torch.from_numpy(a).cuda() for a in (X, h0, c0))
     kw = dict(h0=h0d, c0=c0d) if cell == "lstm" else dict(h0=h0d)
     c_out = torch.empty((N, L), dtype=torch.float32, device="cuda") if cell == "lstm" else None
@@ -100,12 +107,14 @@ def test_zero_copy_sliding_windows_and_wide_inputs(elm):
         model.close()
 
 
-def test_rows_are_independent_of_tiling(elm):
+@pytest.mark.parametrize("mode", MODES)
+def test_rows_are_independent_of_tiling(elm, mode):
     # the same window gives the same row wherever it sits in the batch (bitwise)
     cell, N, Q, d, L = "lstm", 200, 4, 3, 96
     W, U, b = rand_weights(cell, d, L, seed=3)
     X = np.random.default_rng(4).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+    model.set_contraction(mode)
     H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
     perm = np.random.default_rng(5).permutation(N)
     Hp = elm.hidden(model, torch.from_numpy(X[perm].copy()).cuda()).cpu().numpy()
@@ -136,12 +145,13 @@ def test_seeded_weights_match_the_oracle_generator(elm, name):
     model.close()
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ["cfg1", "cfg2"])
-def test_contractive_configs_full_horizon(elm, name):
+def test_contractive_configs_full_horizon(elm, name, mode):
     cfg = synthdata.get_config(name)
     _, X, _ = synthdata.make_problem(cfg)
     model = elm.Model.create(cfg.cell, cfg.Q, cfg.d, cfg.L, cfg.m, cfg.seed, w_scale=cfg.w_scale,
-                             spectral_radius=cfg.spectral_radius)
+                             spectral_radius=cfg.spectral_radius, contraction=mode)
     W, U, b, _ = model.weights()
     H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
     assert_h_close(H, ocells.hidden_chunked(cfg.cell, X, W, U, b))
@@ -159,8 +169,9 @@ def _sample_rows(N, S, seed):
 # (measured with the oracle: cfg3 7.4x at t=8, cfg4 9.2x at t=4, cfg5 3.6x at t=4; at L = 512 a
 # float32 dot product of 521 terms already carries ~1e-6 of rounding per step, which leaves
 # room for 4 steps under the 1e-5 * rms bound)
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name,q_short", [("cfg3", 8), ("cfg4", 4), ("cfg5", 4)])
-def test_full_size_configs_short_horizon_and_step_at_depth(elm, name, q_short):
+def test_full_size_configs_short_horizon_and_step_at_depth(elm, name, q_short, mode):
     """Full N in the benchmark's launch configuration; the oracle checks sampled rows.
 
     These cells amplify a 1e-7 perturbation by orders of magnitude over the full Q, so exact
@@ -173,7 +184,7 @@ def test_full_size_configs_short_horizon_and_step_at_depth(elm, name, q_short):
     N, Q, d, L = cfg.N, cfg.Q, cfg.d, cfg.L
     Xv = torch.as_strided(sd, (N, Q, d), (d, d, 1))
     model = elm.Model.create(cfg.cell, Q, d, L, cfg.m, cfg.seed, w_scale=cfg.w_scale,
-                             forget_bias=cfg.forget_bias, zero_bias=cfg.zero_bias)
+                             forget_bias=cfg.forget_bias, zero_bias=cfg.zero_bias, contraction=mode)
     W, U, b, _ = model.weights()
     rows = _sample_rows(N, 1024, seed=1)
     Xs = np.lib.stride_tricks.sliding_window_view(series, (Q, d))[rows, 0]
@@ -202,3 +213,30 @@ def test_full_size_configs_short_horizon_and_step_at_depth(elm, name, q_short):
                          **({"c0": c32} if c32 is not None else {}))
     assert_h_close(H2, ref2)
     model.close()
+
+
+def test_split_mode_argument_errors_and_awkward_weight_ranges(elm):
+    # d > 15 needs more than one input group: the mode is refused, the model keeps running in float32
+    W, U, b = rand_weights("lstm", 16, 8, seed=1)
+    model = elm.Model.from_weights("lstm", 3, 1, W, U, b)
+    with pytest.raises(elm.ElmRnnError) as ei:
+        model.set_contraction("split16")
+    assert ei.value.code == -5
+    X = np.random.default_rng(2).uniform(-1, 1, (40, 3, 16)).astype(np.float32)
+    assert_h_close(elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy(), ocells.hidden("lstm", X, W, U, b))
+    model.close()
+    # weights and inputs far from unit scale: tiny recurrent weights, large inputs and biases,
+    # one dominant recurrent entry next to many small ones
+    for cell, uscale, xscale, seed in (("elman", 1e-6, 300.0, 3), ("gru", 1.0, 0.01, 4), ("lstm", 0.2, 5000.0, 5)):
+        N, Q, d, L = 100, 3, 3, 48
+        W, U, b = rand_weights(cell, d, L, seed=seed, scale=uscale)
+        W = (W / uscale * (1.0 / xscale)).astype(np.float32)
+        U[0, 0] = np.float32(25.0 * uscale)
+        X = (np.random.default_rng(seed).uniform(-1, 1, (N, Q, d)) * xscale).astype(np.float32)
+        model = elm.Model.from_weights(cell, Q, 1, W, U, b)
+        model.set_contraction("split16")
+        H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+        assert_h_close(H, ocells.hidden(cell, X, W, U, b))
+        model.set_contraction("fp32")          # and back
+        assert_h_close(elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy(), ocells.hidden(cell, X, W, U, b))
+        model.close()
