@@ -83,11 +83,17 @@ __device__ __forceinline__ void store_split_x(char* p, float x) {
 __device__ __forceinline__ int h_col_off(int k) { return (k >> 4) * 64 + ((k >> 3) & 1) * 32 + (k & 7) * 2; }
 __device__ __forceinline__ int x_col_off(int k) { return ((k >> 3) & 1) * 48 + (k & 7) * 2; }
 
-__device__ __forceinline__ float sigmoid_f(float x) {
-    return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+// Activations of a scaled accumulator v = P * a: the factor 1/P is folded into the exponent
+// constants k1 = -log2(e)/P and k2 = 2 log2(e)/P, so sigmoid(a) = 1/(1 + 2^(k1 v)) and
+// tanh(a) = 1 - 2/(1 + 2^(k2 v)) cost one multiply, one v_exp and one v_rcp each.
+__device__ __forceinline__ float sigmoid_s(float v, float k1) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * k1));
+}
+__device__ __forceinline__ float tanh_s(float v, float k2) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * k2));
 }
 __device__ __forceinline__ float tanh_f(float x) {
-    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x));
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.885390081777927f));
 }
 // acc[g][ms] += A(ms) . B(g) over the whole weight stream of one column block.
 //   Stream position 0 and 1: the input group.  Slot 0 holds bf16 pieces (p1, p2) of [W; b] * P, slot 1
@@ -136,6 +142,9 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
         }
     };
 
+    // Register economy: every A fragment is loaded as late as its first use allows and the products
+    // are ordered so that fragments die early (the x pieces one after the other, then per recurrent
+    // group hi before lo), which keeps at most three 4-register fragments per row block live.
     uintx4 a[MS][2];              // (hi, lo) fragment of the current recurrent group
     {
         const char* axp = ap + xoff + (lane >> 5) * 16;      // half*48 in total
@@ -145,25 +154,31 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
 #pragma unroll
             for (int q = 0; q < 3; ++q)
                 x[ms][q] = *reinterpret_cast<const uintx4*>(axp + ms * 32 * stride + q * 16);
-#pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
-            a[ms][0] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride);
-            a[ms][1] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + 16);
-        }
         __builtin_amdgcn_sched_barrier(0);
-        // products kept: p1p1, p1p2, p2p1, p2p2, p1p3, p3p1 (everything above 2^-24 relative)
+        // products kept (smallest first): p3p1, p2p2, p2p1, p1p3, p1p2, p1p1 -- everything above
+        // 2^-24 relative
 #pragma unroll
         for (int c = 0; c < 6; ++c) {
-            const int xa = (c == 2 || c == 3) ? 1 : (c == 5) ? 2 : 0;
-            const int wslot = (c == 4) ? 1 : 0;
-            const int wpiece = (c == 1 || c == 3) ? 1 : 0;
+            const int xa = (c == 0) ? 2 : (c <= 2) ? 1 : 0;
+            const int wslot = (c == 3) ? 1 : 0;
+            const int wpiece = (c == 1 || c == 4) ? 1 : 0;
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
                     acc[g][ms] = mfma_bf16(x[ms][xa], bq[wslot][g][wpiece], acc[g][ms]);
+            if (c == 2) {             // pieces 3 and 2 are dead: fetch hi of the first recurrent group
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    a[ms][0] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+            a[ms][1] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + 16);
         if (PF < KGs) refill(0, PF);
         if (PF + 1 < KGs) refill(1, PF + 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -171,30 +186,34 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
 
     const int KGh = KGs - 2;
     auto group = [&](int p, int u, bool do_refill) {
-        uintx4 an[MS][2];            // fragment of the next recurrent group
         const int kg = p - 2;
         const int kn = (kg + 1 < KGh) ? (kg + 1) : kg;
+        uintx4 an[MS];               // hi fragment of the next recurrent group
 #pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
-            an[ms][0] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + kn * 64);
-            an[ms][1] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + kn * 64 + 16);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {          // hi*hi, hi*lo, lo*hi
+        for (int c = 0; c < 2; ++c) {          // hi*lo, hi*hi
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
-                    acc[g][ms] = mfma_f16(a[ms][c == 2 ? 1 : 0], bq[u][g][c == 1 ? 1 : 0], acc[g][ms]);
+                    acc[g][ms] = mfma_f16(a[ms][0], bq[u][g][c == 0 ? 1 : 0], acc[g][ms]);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (do_refill) refill(u, p + PF);
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+            an[ms] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + kn * 64);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < G; ++g)            // lo*hi
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+                acc[g][ms] = mfma_f16(a[ms][1], bq[u][g][0], acc[g][ms]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) {
-            a[ms][0] = an[ms][0];
-            a[ms][1] = an[ms][1];
+            a[ms][1] = *reinterpret_cast<const uintx4*>(ap + ms * 32 * stride + kn * 64 + 16);
+            a[ms][0] = an[ms];
         }
+        if (do_refill) refill(u, p + PF);
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -223,12 +242,15 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const char* __r
 
 // STAGE > 0: that many of a lane's pending new-h values (those of the first column chunk) wait in
 // spare LDS instead of registers; used by the largest LSTM variants, which otherwise spill.
+// In the two-pass LSTM variants the pending new-h values of the middle column chunks (1 .. NCH-2)
+// do not wait in registers either: they are written to their final place in H (rows private to the
+// work-group) and read back, all loads in flight at once, when the operand is rebuilt.
 template <int CELL, int MS, int NCH, int STAGE>
 __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs p) {
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS;
     constexpr int PF = 4;
-    constexpr int PF2 = 5;
+    constexpr int PF2 = 4;
     constexpr bool TWOPASS = (CELL == ELM_CELL_LSTM) && (NCH >= 3);
     extern __shared__ __align__(16) char lds[];
 
@@ -236,7 +258,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     // wave-uniform values are forced into scalar registers: weight addresses then live in SGPRs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = p.L, d = p.d, KGs = p.KGs, stride = p.stride, xoff = p.xoff;
-    const float inv = p.inv_scale;
+    const float k1 = -1.4426950408889634f * p.inv_scale, k2 = 2.885390081777927f * p.inv_scale;
     const int64_t row0 = (int64_t)blockIdx.x * S;
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
@@ -335,6 +357,12 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 
     // lane part of the operand address of this lane's accumulator columns (rows 4*(lane>>5) + ...)
     const int lane_base0 = (4 * (lane >> 5)) * stride + h_col_off(col_in);
+    // the tile's rows of H as a range-checked buffer (rows past N are dropped by the hardware);
+    // element (row, col) of this lane's accumulators sits at hvoff + jb*128 + row_in_tile*L*4
+    const int64_t rows_here = (p.N - row0 < S) ? (p.N - row0) : S;
+    const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
+        p.H + row0 * L, 0, (int)(rows_here * L * 4), 0x00020000);
+    const unsigned hvoff = (unsigned)((4 * (lane >> 5)) * L + col_in) * 4u;
 
     for (int t = 0; t < p.Q_run; ++t) {
         if (CELL == ELM_CELL_GRU) {
@@ -369,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) {
-                                ig_gg[ms][i] = sigmoid_f(acc[0][ms][i] * inv) * tanh_f(acc[1][ms][i] * inv);
+                                ig_gg[ms][i] = sigmoid_s(acc[0][ms][i], k1) * tanh_s(acc[1][ms][i], k2);
                                 acc[0][ms][i] = 0.0f;
                                 acc[1][ms][i] = 0.0f;
                             }
@@ -379,11 +407,18 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) {
-                                const float c = sigmoid_f(acc[0][ms][i] * inv) * st[ch][ms][i] + ig_gg[ms][i];
+                                const float c = sigmoid_s(acc[0][ms][i], k1) * st[ch][ms][i] + ig_gg[ms][i];
                                 st[ch][ms][i] = c;
-                                const float hv = sigmoid_f(acc[1][ms][i] * inv) * tanh_f(c);
-                                if (ch == 0 && ms * 16 + i < STAGE) stage[(ms * 16 + i) * kThreads] = hv;
-                                else hn[ch][ms][i] = hv;
+                                const float hv = sigmoid_s(acc[1][ms][i], k1) * tanh_f(c);
+                                if (ch == 0 && ms * 16 + i < STAGE) {
+                                    stage[(ms * 16 + i) * kThreads] = hv;
+                                } else if (ch >= 1 && ch < NCH - 1) {
+                                    __builtin_amdgcn_raw_buffer_store_b32(
+                                        __builtin_bit_cast(unsigned, hv), hrs, hvoff + (unsigned)jb * 128u,
+                                        (unsigned)((ms * 32 + 8 * (i >> 2) + (i & 3)) * L) * 4u, 0);
+                                } else {
+                                    hn[ch][ms][i] = hv;
+                                }
                             }
                     } else {
                         floatx16 acc[G][MS];
@@ -399,12 +434,12 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
                             for (int i = 0; i < 16; ++i) {
                                 if (CELL == ELM_CELL_ELMAN) {
-                                    hn[ch][ms][i] = tanh_f(acc[0][ms][i] * inv);
+                                    hn[ch][ms][i] = tanh_s(acc[0][ms][i], k2);
                                 } else {
-                                    const float ig = sigmoid_f(acc[0][ms][i] * inv);
-                                    const float fg = sigmoid_f(acc[G > 1 ? 1 : 0][ms][i] * inv);
-                                    const float og = sigmoid_f(acc[G > 2 ? 2 : 0][ms][i] * inv);
-                                    const float gg = tanh_f(acc[G > 3 ? 3 : 0][ms][i] * inv);
+                                    const float ig = sigmoid_s(acc[0][ms][i], k1);
+                                    const float fg = sigmoid_s(acc[G > 1 ? 1 : 0][ms][i], k1);
+                                    const float og = sigmoid_s(acc[G > 2 ? 2 : 0][ms][i], k1);
+                                    const float gg = tanh_s(acc[G > 3 ? 3 : 0][ms][i], k2);
                                     const float c = fg * st[ch][ms][i] + ig * gg;
                                     st[ch][ms][i] = c;
                                     hn[ch][ms][i] = og * tanh_f(c);
@@ -425,13 +460,29 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                     const int col = jb * 32 + col_in;
                     if (jb < p.nJB && col < L) {
                         char* dst = A0 + lane_base + jb * 128;
+                        if (TWOPASS && ch >= 1 && ch < NCH - 1) {
+                            float back[MS][16];
 #pragma unroll
-                        for (int ms = 0; ms < MS; ++ms)
+                            for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                            for (int i = 0; i < 16; ++i)
-                                store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride,
-                                              (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads]
-                                                                               : hn[ch][ms][i]);
+                                for (int i = 0; i < 16; ++i)
+                                    back[ms][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                        hrs, hvoff + (unsigned)jb * 128u,
+                                        (unsigned)((ms * 32 + 8 * (i >> 2) + (i & 3)) * L) * 4u, 0));
+#pragma unroll
+                            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i)
+                                    store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, back[ms][i]);
+                        } else {
+#pragma unroll
+                            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i)
+                                    store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride,
+                                                  (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads]
+                                                                                   : hn[ch][ms][i]);
+                        }
                     }
                 }
                 if (x_prefetch) store_x(A0); else copy_x_direct(t + 1, A0);
@@ -457,8 +508,8 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
-                            hn[ch][ms][i] = sigmoid_f(acc[0][ms][i] * inv);
-                            const float r = sigmoid_f(acc[1][ms][i] * inv);
+                            hn[ch][ms][i] = sigmoid_s(acc[0][ms][i], k1);
+                            const float r = sigmoid_s(acc[1][ms][i], k1);
                             if (col < L)
                                 store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, r * st[ch][ms][i]);
                         }
@@ -483,7 +534,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
                             const float z = hn[ch][ms][i];
-                            const float hv = (1.0f - z) * st[ch][ms][i] + z * tanh_f(acc[0][ms][i] * inv);
+                            const float hv = (1.0f - z) * st[ch][ms][i] + z * tanh_s(acc[0][ms][i], k2);
                             st[ch][ms][i] = hv;
                             if (col < L && more)
                                 store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, hv);
@@ -504,12 +555,17 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
         const int jb = ch * 4 + wave;
         const int col = jb * 32 + col_in;
         if (jb < p.nJB && col < L) {
+            const bool in_place = TWOPASS && ch >= 1 && ch < NCH - 1;      // H already holds these
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int64_t row = row0 + acc_row(ms, i);
                     if (row < p.N) {
+                        if (in_place) {
+                            if (CELL == ELM_CELL_LSTM && p.C != nullptr) p.C[row * L + col] = st[ch][ms][i];
+                            continue;
+                        }
                         float hv;
                         if (CELL == ELM_CELL_GRU) hv = st[ch][ms][i];
                         else hv = (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads] : hn[ch][ms][i];
