@@ -4,7 +4,13 @@
 A "step" is one whole fit (weights from the seed -> hidden matrix H(Q) -> TSQR solve with
 refinement) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--contraction fp32]
+                    [--no-fast-mode] [--no-cpu-baseline]
+
+The reported line is for --contraction (default fp32: float32 matrix instructions, the arithmetic the
+configurations name).  Unless --no-fast-mode is given, the same K steps are then timed once more
+in the library's other stage-1 mode (split16: the recurrent contraction as an fp16 hi/lo split on
+fp16 matrix instructions, float32-equivalent accuracy) and reported under "fast_mode".
 
 Workload: the LSTM N = 4M, Q = 100, d = 8, L = 512, m = 2 configuration (the one the headline
 metric is quoted on); other configurations can be selected for study with --config.
@@ -26,12 +32,14 @@ import synthdata  # noqa: E402
 
 GATES = {"elman": 1, "lstm": 4, "gru": 3}
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
+PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
 
 # Memory traffic of one hidden-matrix kernel launch, bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (profiles/ holds the summaries these come from).  The
 # counters sit at the L2 boundary: they include refills of the L2-resident weight operand from the
 # Infinity Cache, which never reach HBM.
 MEASURED_TRAFFIC_BYTES = {"cfg5": 922.8e9 + 39.1e9}   # profiles/hidden_kernel_cfg5_pmc.txt (L2-boundary traffic)
+MEASURED_TRAFFIC_SPLIT_BYTES = {}                       # profiles/hidden_split_kernel_cfg5_pmc.txt
 
 
 def stage1_flops(cfg) -> float:
@@ -67,6 +75,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="cfg5")
+    ap.add_argument("--contraction", default="fp32", choices=["fp32", "split16"],
+                    help="stage-1 contraction mode of the reported line")
+    ap.add_argument("--no-fast-mode", action="store_true", help="skip the extra split16 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
@@ -97,11 +108,27 @@ def main() -> int:
     kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
               zero_bias=cfg.zero_bias, workspace=ws, H_out=H)
 
-    def step():
-        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)
+    def step(mode=args.contraction):
+        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, contraction=mode, **kw)
         st = res.stats
         res.model.close()
         return st
+
+    def roofline(mode, hidden_ms):
+        achieved = stage1_flops(cfg) / (hidden_ms * 1e-3) / 1e12
+        if mode == "fp32":
+            return {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                    "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"}
+        # three fp16 matrix instructions per algorithmic product (hi*hi, hi*lo, lo*hi): the
+        # algorithmic rate can reach at most a third of the fp16 peak
+        return {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_MFMA_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_SPLIT_BYTES.get(cfg.name),
+                "kernel": "hidden_split_kernel (stage 1, fp16 MFMA 32x32x16, 3 products per float32 product)",
+                "issued_over_algorithmic": 3.0 * (16 * ((cfg.L + 15) // 16) + 32) / (cfg.L + cfg.d),
+                "achieved_over_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
 
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -121,7 +148,6 @@ def main() -> int:
     ms_per_step = 1e3 * dt / args.steps
     hidden_ms = float(np.mean([s.t_hidden_ms for s in stats]))     # HIP events on the launch stream
     solve_ms = float(np.mean([s.t_solve_ms for s in stats]))
-    achieved = stage1_flops(cfg) / (hidden_ms * 1e-3) / 1e12
     out = {
         "metric": "ELM fit samples/sec (H build + TSQR solve) at 1 GPU",
         "value": cfg.N * args.steps / dt,
@@ -133,19 +159,30 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32" if args.contraction == "fp32" else "f32 (fp16 hi/lo split operands, f32 accumulate)",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.cell} ELM-RNN fit, N={cfg.N}, Q={cfg.Q}, d={cfg.d}, "
                                f"L={cfg.L}, m={cfg.m}, materialised windows resident in HBM",
                    "hidden_ms": hidden_ms, "solve_ms": solve_ms,
                    "hidden_samples_per_s": cfg.N / (hidden_ms * 1e-3),
                    "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
+                   "contraction": args.contraction,
                    "rmse": stats[-1].rmse, "ne_resid": stats[-1].ne_resid},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                     "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"},
+        "roofline": roofline(args.contraction, hidden_ms),
     }
+    if not args.no_fast_mode and args.contraction == "fp32" and cfg.d <= 15:
+        step("split16")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fstats = [step("split16") for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        f_hidden = float(np.mean([s.t_hidden_ms for s in fstats]))
+        f_solve = float(np.mean([s.t_solve_ms for s in fstats]))
+        out["fast_mode"] = {"contraction": "split16", "value": cfg.N * args.steps / fdt, "unit": "samples/s",
+                            "ms_per_step": 1e3 * fdt / args.steps, "hidden_ms": f_hidden, "solve_ms": f_solve,
+                            "rmse": fstats[-1].rmse, "ne_resid": fstats[-1].ne_resid,
+                            "roofline": roofline("split16", f_hidden)}
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
                                  "cfg5": 4096}[cfg.name]

@@ -68,6 +68,19 @@ __device__ __forceinline__ void store_split_h(char* p, float v) {
     *reinterpret_cast<_Float16*>(p) = hi;
     *reinterpret_cast<_Float16*>(p + 16) = lo;
 }
+// four consecutive recurrent columns of one row (first column a multiple of 4): 8-byte stores
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_split_h4(char* p, float v0, float v1, float v2, float v3) {
+    const float s[4] = {v0 * kHScale, v1 * kHScale, v2 * kHScale, v3 * kHScale};
+    halfx4 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        hi[e] = (_Float16)s[e];
+        lo[e] = (_Float16)(s[e] - (float)hi[e]);
+    }
+    *reinterpret_cast<halfx4*>(p) = hi;
+    *reinterpret_cast<halfx4*>(p + 16) = lo;
+}
 // x = p1 + p2 + p3 exactly, each piece a bf16 (truncation keeps 8 significant bits per piece)
 __device__ __forceinline__ void store_split_x(char* p, float x) {
     const unsigned u1 = __builtin_bit_cast(unsigned, x) & 0xFFFF0000u;
@@ -166,7 +179,7 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
-                    acc[g][ms] = mfma_bf16(x[ms][xa], bq[wslot][g][wpiece], acc[g][ms]);
+                    acc[g][ms] = mfma_bf16(bq[wslot][g][wpiece], x[ms][xa], acc[g][ms]);
             if (c == 2) {             // pieces 3 and 2 are dead: fetch hi of the first recurrent group
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -195,7 +208,7 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
-                    acc[g][ms] = mfma_f16(a[ms][0], bq[u][g][c == 0 ? 1 : 0], acc[g][ms]);
+                    acc[g][ms] = mfma_f16(bq[u][g][c == 0 ? 1 : 0], a[ms][0], acc[g][ms]);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -206,7 +219,7 @@ __device__ __forceinline__ void contract_main(floatx16 (&acc)[G][MS], uintx4 (&b
         for (int g = 0; g < G; ++g)            // lo*hi
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
-                acc[g][ms] = mfma_f16(a[ms][1], bq[u][g][0], acc[g][ms]);
+                acc[g][ms] = mfma_f16(bq[u][g][0], a[ms][1], acc[g][ms]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) {
@@ -242,16 +255,18 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const char* __r
 
 // STAGE > 0: that many of a lane's pending new-h values (those of the first column chunk) wait in
 // spare LDS instead of registers; used by the largest LSTM variants, which otherwise spill.
-// In the two-pass LSTM variants the pending new-h values of the middle column chunks (1 .. NCH-2)
-// do not wait in registers either: they are written to their final place in H (rows private to the
-// work-group) and read back, all loads in flight at once, when the operand is rebuilt.
+// In the LSTM variants with three or four column chunks the pending new-h values of the middle
+// chunks (1 .. NCH-2) do not wait in registers either: they are parked in the tile's own rows of H (private to the
+// work-group until the last step, which writes them in place) and read back, all loads in flight at
+// once, when the operand is rebuilt.
 template <int CELL, int MS, int NCH, int STAGE>
 __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs p) {
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS;
-    constexpr int PF = 4;
-    constexpr int PF2 = 4;
-    constexpr bool TWOPASS = (CELL == ELM_CELL_LSTM) && (NCH >= 3);
+    // fragment-queue depth; the widest LSTM variants have 24 matrix instructions per group and
+    // the fewest spare registers: three groups in flight cover the L2 latency there
+    constexpr int PF = (CELL == ELM_CELL_LSTM && NCH >= 3) ? 3 : 4;
+    constexpr bool GSTAGE = (CELL == ELM_CELL_LSTM) && (NCH >= 3);   // middle chunks parked in H
     extern __shared__ __align__(16) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -267,9 +282,14 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     char* A1 = lds + S * stride;        // GRU only: (r*h_{t-1}) | x_t | 1, split
     float* stage = reinterpret_cast<float*>(lds + nbuf * S * stride) + tid;   // STAGE > 0: [STAGE][256]
 
-    // accumulator element (ms, i) of this lane: sample row, hidden column inside the block
-    const int col_in = lane & 31;
-    auto acc_row = [&](int ms, int i) { return ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
+    // The weights sit on the M side of the matrix instruction and the samples on the N side, so
+    // accumulator element (ms, i) of this lane belongs to sample row ms*32 + (lane & 31) and to
+    // hidden column 8*(i>>2) + 4*(lane>>5) + (i&3) of the 32-column block: every group of four
+    // elements i = 4q..4q+3 is four consecutive columns of one row (8-byte operand stores).
+    const int samp_in = lane & 31;
+    const int unit0 = 4 * (lane >> 5);
+    auto acc_unit = [&](int i) { return 8 * (i >> 2) + unit0 + (i & 3); };
+    const int Lp = p.KGs * 16 - 32;      // recurrent columns the operand row has room for
 
     // ---- initial contents of the activation operand: h = 0, x = 0, the bias column = 1 (piece 1)
     {
@@ -328,13 +348,13 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         const int jb = ch * 4 + wave;
-        const int col = jb * 32 + col_in;
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float v = 0.0f;
-                const int64_t row = row0 + acc_row(ms, i);
+                const int64_t row = row0 + ms * 32 + samp_in;
+                const int col = jb * 32 + acc_unit(i);
                 const float* src = (CELL == ELM_CELL_LSTM) ? p.c0 : (CELL == ELM_CELL_GRU) ? p.h0 : nullptr;
                 if (src != nullptr && row < p.N && col < L) v = src[row * L + col];
                 st[ch][ms][i] = v;
@@ -351,18 +371,19 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     }
     __syncthreads();
 
-    uintx4 bq2[PF2][2][2];     // weight-fragment queue of the two-pass LSTM path (lives across phases)
-    if (TWOPASS && wave < p.nJB)
-        prefetch_weights<2, 4, 0, 3, PF2>(bq2, wrs, (unsigned)(wave * KGs * G) * 2048u, lane);
-
-    // lane part of the operand address of this lane's accumulator columns (rows 4*(lane>>5) + ...)
-    const int lane_base0 = (4 * (lane >> 5)) * stride + h_col_off(col_in);
+    // lane part of the operand address of this lane's accumulator elements: row samp_in, first
+    // column unit0 of the block; element group (ms, q) adds ms*32*stride + jb*128 + h_col_off(8q)
+    const int lane_base0 = samp_in * stride + unit0 * 2;
     // the tile's rows of H as a range-checked buffer (rows past N are dropped by the hardware);
-    // element (row, col) of this lane's accumulators sits at hvoff + jb*128 + row_in_tile*L*4
+    // element group (ms, q) of column block jb sits at hvoff + (ms*32*L + jb*32 + 8q)*4
     const int64_t rows_here = (p.N - row0 < S) ? (p.N - row0) : S;
     const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
         p.H + row0 * L, 0, (int)(rows_here * L * 4), 0x00020000);
-    const unsigned hvoff = (unsigned)((4 * (lane >> 5)) * L + col_in) * 4u;
+    const unsigned hvoff = (unsigned)(samp_in * L + unit0) * 4u;
+    // Between steps a full tile keeps the staged values in a packed order instead (value e of
+    // thread tid at e*1024 + tid*4: every wave store is one contiguous 256 bytes); the last step and
+    // a ragged last tile use the true H layout.  (NCH-2)*MS*16 KB always fit the tile's S*L*4 bytes.
+    const bool packed_stage = GSTAGE && rows_here == S;
 
     for (int t = 0; t < p.Q_run; ++t) {
         if (CELL == ELM_CELL_GRU) {
@@ -377,50 +398,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                 const int jb = ch * 4 + wave;
                 if (jb < p.nJB) {
                     const unsigned wbase = (unsigned)(jb * KGs * G) * 2048u;
-                    if (TWOPASS) {
-                        // LSTM with many column chunks: two contractions of two gates each keep the
-                        // accumulators at 64 registers so that c and the pending h stay in registers
-                        floatx16 acc[2][MS];
-                        float ig_gg[MS][16];
-#pragma unroll
-                        for (int g = 0; g < 2; ++g)
-#pragma unroll
-                            for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                                for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                        // the weight queue of each contraction is filled one phase early (before the
-                        // point-wise work of the previous contraction), so the first MFMA never waits
-                        const int jn = ((ch + 1 < NCH) && ((ch + 1) * 4 + wave < p.nJB)) ? jb + 4 : wave;
-                        contract_main<2, 4, 0, 3, MS, PF2>(acc, bq2, A0, stride, xoff, wrs, wbase, KGs, lane);   // gates i, g
-                        prefetch_weights<2, 4, 1, 1, PF2>(bq2, wrs, wbase, lane);
-#pragma unroll
-                        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                ig_gg[ms][i] = sigmoid_s(acc[0][ms][i], k1) * tanh_s(acc[1][ms][i], k2);
-                                acc[0][ms][i] = 0.0f;
-                                acc[1][ms][i] = 0.0f;
-                            }
-                        contract_main<2, 4, 1, 1, MS, PF2>(acc, bq2, A0, stride, xoff, wrs, wbase, KGs, lane);   // gates f, o
-                        prefetch_weights<2, 4, 0, 3, PF2>(bq2, wrs, (unsigned)(jn * KGs * G) * 2048u, lane);
-#pragma unroll
-                        for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                const float c = sigmoid_s(acc[0][ms][i], k1) * st[ch][ms][i] + ig_gg[ms][i];
-                                st[ch][ms][i] = c;
-                                const float hv = sigmoid_s(acc[1][ms][i], k1) * tanh_f(c);
-                                if (ch == 0 && ms * 16 + i < STAGE) {
-                                    stage[(ms * 16 + i) * kThreads] = hv;
-                                } else if (ch >= 1 && ch < NCH - 1) {
-                                    __builtin_amdgcn_raw_buffer_store_b32(
-                                        __builtin_bit_cast(unsigned, hv), hrs, hvoff + (unsigned)jb * 128u,
-                                        (unsigned)((ms * 32 + 8 * (i >> 2) + (i & 3)) * L) * 4u, 0);
-                                } else {
-                                    hn[ch][ms][i] = hv;
-                                }
-                            }
-                    } else {
+                    {
                         floatx16 acc[G][MS];
 #pragma unroll
                         for (int g = 0; g < G; ++g)
@@ -442,7 +420,18 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                                     const float gg = tanh_s(acc[G > 3 ? 3 : 0][ms][i], k2);
                                     const float c = fg * st[ch][ms][i] + ig * gg;
                                     st[ch][ms][i] = c;
-                                    hn[ch][ms][i] = og * tanh_f(c);
+                                    const float hv = og * tanh_f(c);
+                                    if (ch == 0 && ms * 16 + i < STAGE) {
+                                        stage[(ms * 16 + i) * kThreads] = hv;
+                                    } else if (GSTAGE && ch >= 1 && ch < NCH - 1) {
+                                        const bool packed = packed_stage && more;     // uniform
+                                        __builtin_amdgcn_raw_buffer_store_b32(
+                                            __builtin_bit_cast(unsigned, hv), hrs, packed ? tid * 4u : hvoff,
+                                            packed ? (unsigned)((ch - 1) * MS * 16 + ms * 16 + i) * 1024u
+                                                   : (unsigned)(ms * 32 * L + jb * 32 + 8 * (i >> 2) + (i & 3)) * 4u, 0);
+                                    } else {
+                                        hn[ch][ms][i] = hv;
+                                    }
                                 }
                             }
                     }
@@ -457,32 +446,29 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
                     const int jb = ch * 4 + wave;
-                    const int col = jb * 32 + col_in;
-                    if (jb < p.nJB && col < L) {
+                    if (jb < p.nJB) {
                         char* dst = A0 + lane_base + jb * 128;
-                        if (TWOPASS && ch >= 1 && ch < NCH - 1) {
-                            float back[MS][16];
+                        float v[MS][16];
 #pragma unroll
-                            for (int ms = 0; ms < MS; ++ms)
+                        for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                                for (int i = 0; i < 16; ++i)
-                                    back[ms][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                        hrs, hvoff + (unsigned)jb * 128u,
-                                        (unsigned)((ms * 32 + 8 * (i >> 2) + (i & 3)) * L) * 4u, 0));
+                            for (int i = 0; i < 16; ++i) {
+                                if (GSTAGE && ch >= 1 && ch < NCH - 1)
+                                    v[ms][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                        hrs, packed_stage ? tid * 4u : hvoff,
+                                        packed_stage ? (unsigned)((ch - 1) * MS * 16 + ms * 16 + i) * 1024u
+                                                     : (unsigned)(ms * 32 * L + jb * 32 + 8 * (i >> 2) + (i & 3)) * 4u, 0));
+                                else
+                                    v[ms][i] = (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads]
+                                                                                : hn[ch][ms][i];
+                            }
 #pragma unroll
-                            for (int ms = 0; ms < MS; ++ms)
+                        for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                                for (int i = 0; i < 16; ++i)
-                                    store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, back[ms][i]);
-                        } else {
-#pragma unroll
-                            for (int ms = 0; ms < MS; ++ms)
-#pragma unroll
-                                for (int i = 0; i < 16; ++i)
-                                    store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride,
-                                                  (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads]
-                                                                                   : hn[ch][ms][i]);
-                        }
+                            for (int q = 0; q < 4; ++q)
+                                if (jb * 32 + 8 * q < Lp)
+                                    store_split_h4(dst + ms * 32 * stride + h_col_off(8 * q), v[ms][4 * q],
+                                                   v[ms][4 * q + 1], v[ms][4 * q + 2], v[ms][4 * q + 3]);
                     }
                 }
                 if (x_prefetch) store_x(A0); else copy_x_direct(t + 1, A0);
@@ -493,7 +479,6 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
                 const int jb = ch * 4 + wave;
-                const int col = jb * 32 + col_in;
                 if (jb < p.nJB) {
                     floatx16 acc[2][MS];
 #pragma unroll
@@ -507,11 +492,16 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            hn[ch][ms][i] = sigmoid_s(acc[0][ms][i], k1);
-                            const float r = sigmoid_s(acc[1][ms][i], k1);
-                            if (col < L)
-                                store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, r * st[ch][ms][i]);
+                        for (int q = 0; q < 4; ++q) {
+                            float rh[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int i = 4 * q + e;
+                                hn[ch][ms][i] = sigmoid_s(acc[0][ms][i], k1);
+                                rh[e] = sigmoid_s(acc[1][ms][i], k1) * st[ch][ms][i];
+                            }
+                            if (jb * 32 + 8 * q < Lp)
+                                store_split_h4(dst + ms * 32 * stride + h_col_off(8 * q), rh[0], rh[1], rh[2], rh[3]);
                         }
                 }
             }
@@ -520,7 +510,6 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
                 const int jb = ch * 4 + wave;
-                const int col = jb * 32 + col_in;
                 if (jb < p.nJB) {
                     floatx16 acc[1][MS];
 #pragma unroll
@@ -532,12 +521,16 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float z = hn[ch][ms][i];
-                            const float hv = (1.0f - z) * st[ch][ms][i] + z * tanh_s(acc[0][ms][i], k2);
-                            st[ch][ms][i] = hv;
-                            if (col < L && more)
-                                store_split_h(dst + (ms * 32 + 8 * (i >> 2) + (i & 3)) * stride, hv);
+                        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int i = 4 * q + e;
+                                const float z = hn[ch][ms][i];
+                                st[ch][ms][i] = (1.0f - z) * st[ch][ms][i] + z * tanh_s(acc[0][ms][i], k2);
+                            }
+                            if (more && jb * 32 + 8 * q < Lp)
+                                store_split_h4(dst + ms * 32 * stride + h_col_off(8 * q), st[ch][ms][4 * q],
+                                               st[ch][ms][4 * q + 1], st[ch][ms][4 * q + 2], st[ch][ms][4 * q + 3]);
                         }
                 }
             }
@@ -548,28 +541,25 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
         }
     }
 
-    // ---- H(Q) (and the LSTM cell state) straight from the float32 registers: a lane group of 32
-    // writes one 128-byte row segment
+    // ---- H(Q) (and the LSTM cell state) straight from the float32 registers
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         const int jb = ch * 4 + wave;
-        const int col = jb * 32 + col_in;
-        if (jb < p.nJB && col < L) {
-            const bool in_place = TWOPASS && ch >= 1 && ch < NCH - 1;      // H already holds these
+        if (jb < p.nJB) {
+            const bool in_place = GSTAGE && ch >= 1 && ch < NCH - 1;      // H already holds these
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int64_t row = row0 + acc_row(ms, i);
-                    if (row < p.N) {
-                        if (in_place) {
-                            if (CELL == ELM_CELL_LSTM && p.C != nullptr) p.C[row * L + col] = st[ch][ms][i];
-                            continue;
+                    const int64_t row = row0 + ms * 32 + samp_in;
+                    const int col = jb * 32 + acc_unit(i);
+                    if (row < p.N && col < L) {
+                        if (!in_place) {
+                            float hv;
+                            if (CELL == ELM_CELL_GRU) hv = st[ch][ms][i];
+                            else hv = (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads] : hn[ch][ms][i];
+                            p.H[row * L + col] = hv;
                         }
-                        float hv;
-                        if (CELL == ELM_CELL_GRU) hv = st[ch][ms][i];
-                        else hv = (ch == 0 && ms * 16 + i < STAGE) ? stage[(ms * 16 + i) * kThreads] : hn[ch][ms][i];
-                        p.H[row * L + col] = hv;
                         if (CELL == ELM_CELL_LSTM && p.C != nullptr) p.C[row * L + col] = st[ch][ms][i];
                     }
                 }
@@ -592,7 +582,7 @@ constexpr int kStage = 24;      // staged values per lane: 24 KB of LDS per work
 template <int CELL, int MS>
 hipError_t launch_nch(int nch, const SplitArgs& a, int64_t tiles, size_t lds, size_t lds_max,
                       hipStream_t s) {
-    // the two-pass LSTM variants take the LDS staging when the operand leaves room for it
+    // the widest LSTM variants take the LDS staging when the operand leaves room for it
     const size_t staged = lds + (size_t)kStage * kThreads * sizeof(float);
     const bool stage = (CELL == ELM_CELL_LSTM) && MS == 2 && nch >= 3 && staged <= lds_max;
     switch (nch) {

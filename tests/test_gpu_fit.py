@@ -29,12 +29,16 @@ def h_bound_ok(got, ref, tol=1e-5):
     return np.all(np.abs(got - ref) <= tol * np.maximum(np.abs(ref), rms))
 
 
+MODES = ["fp32", "split16"]     # how stage 1 carries the recurrent contraction; same bars for both
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ["cfg1", "cfg2"])
-def test_fit_elman_configs_against_oracle(elm, name):
+def test_fit_elman_configs_against_oracle(elm, name, mode):
     cfg = synthdata.get_config(name)
     _, X, T = synthdata.make_problem(cfg)
     Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
-    res = elm.fit(cfg.cell, Xd, Td, cfg.L, cfg.seed, **cfg_kwargs(cfg))
+    res = elm.fit(cfg.cell, Xd, Td, cfg.L, cfg.seed, contraction=mode, **cfg_kwargs(cfg))
     W, U, b, beta_model = res.model.weights()
     H = res.H.cpu().numpy()
     Href = ocells.hidden_chunked(cfg.cell, X, W, U, b)
@@ -62,8 +66,9 @@ def test_fit_elman_configs_against_oracle(elm, name):
     res.model.close()
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name,N", [("cfg3", None), ("cfg4", 200_000), ("cfg5", 100_000)])
-def test_fit_gated_configs_properties(elm, name, N):
+def test_fit_gated_configs_properties(elm, name, N, mode):
     """LSTM / GRU configurations (cfg4 / cfg5 at reduced N here; full N in the dedicated test)."""
     cfg = synthdata.get_config(name)
     n = cfg.N if N is None else N
@@ -71,7 +76,7 @@ def test_fit_gated_configs_properties(elm, name, N):
     sd = torch.from_numpy(series).cuda()
     Xv = torch.as_strided(sd, (n, cfg.Q, cfg.d), (cfg.d, cfg.d, 1))
     Td = torch.from_numpy(T).cuda()
-    res = elm.fit(cfg.cell, Xv, Td, cfg.L, cfg.seed, **cfg_kwargs(cfg))
+    res = elm.fit(cfg.cell, Xv, Td, cfg.L, cfg.seed, contraction=mode, **cfg_kwargs(cfg))
     H64 = res.H.double()
     b64 = res.beta64
     r = H64 @ b64 - Td.double()
@@ -112,14 +117,15 @@ def test_fit_gated_configs_properties(elm, name, N):
     res.model.close()
 
 
-def test_fit_cfg5_full_size(elm):
+@pytest.mark.parametrize("mode", MODES)
+def test_fit_cfg5_full_size(elm, mode):
     """The headline configuration at full size, as bench.py launches it (materialised windows)."""
     cfg = synthdata.get_config("cfg5")
     series, _, T = synthdata.make_problem(cfg, materialise=False)
     sd = torch.from_numpy(series).cuda()
     Xd = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1)).contiguous()
     Td = torch.from_numpy(T).cuda()
-    res = elm.fit(cfg.cell, Xd, Td, cfg.L, cfg.seed, **cfg_kwargs(cfg))
+    res = elm.fit(cfg.cell, Xd, Td, cfg.L, cfg.seed, contraction=mode, **cfg_kwargs(cfg))
     del Xd
     b64 = res.beta64
     # properties that hold at any size, evaluated in float64 on the device in row chunks
