@@ -39,7 +39,7 @@ PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
 # counters sit at the L2 boundary: they include refills of the L2-resident weight operand from the
 # Infinity Cache, which never reach HBM.
 MEASURED_TRAFFIC_BYTES = {"cfg5": 922.8e9 + 39.1e9}   # profiles/hidden_kernel_cfg5_pmc.txt (L2-boundary traffic)
-MEASURED_TRAFFIC_SPLIT_BYTES = {}                       # profiles/hidden_split_kernel_cfg5_pmc.txt
+MEASURED_TRAFFIC_SPLIT_BYTES = {"cfg5": 1283.1e9 + 413.7e9}   # profiles/fit_cfg5_split16_kernel_trace_and_pmc.txt
 
 
 def stage1_flops(cfg) -> float:
