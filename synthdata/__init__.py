@@ -5,8 +5,8 @@ table of benchmark configurations).  It contains none of the method's
 arithmetic (no cell recurrence, no weight generation, no least squares) and is
 the only code shared by the CPU oracle's tests and the GPU path's tests.
 """
-from .series import (CONFIGS, ElmConfig, make_series, make_windows,
+from .series import (CONFIGS, EXTRA_CONFIGS, ElmConfig, make_series, make_windows,
                      make_problem, get_config)
 
-__all__ = ["CONFIGS", "ElmConfig", "make_series", "make_windows",
+__all__ = ["CONFIGS", "EXTRA_CONFIGS", "ElmConfig", "make_series", "make_windows",
            "make_problem", "get_config"]

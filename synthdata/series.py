@@ -29,7 +29,7 @@ from scipy.signal import lfilter
 @dataclass(frozen=True)
 class ElmConfig:
     name: str
-    cell: str            # "elman" | "lstm" | "gru"
+    cell: str            # "elman" | "lstm" | "gru" | "elman_diag"
     N: int               # number of windows (training samples)
     Q: int               # steps per window
     d: int               # input channels
@@ -52,8 +52,16 @@ CONFIGS = (
 )
 
 
+# Workloads beyond the five benchmark configurations (same generator): the paper's own Elman cell
+# (diagonal feedback over all earlier steps) at the shape of its largest runs (about 1e6 instances,
+# Q = 50, M = 100, univariate).
+EXTRA_CONFIGS = (
+    ElmConfig("paper_elman", "elman_diag", 1_000_000, 50, 1, 100, 1, 0.3, 0.0, 0.0, False, 0.05, 13257),
+)
+
+
 def get_config(name: str) -> ElmConfig:
-    for c in CONFIGS:
+    for c in CONFIGS + EXTRA_CONFIGS:
         if c.name == name:
             return c
     raise KeyError(name)
