@@ -73,6 +73,77 @@ def cpu_baseline(cfg, budget_rows: int):
                       f"windows of {cfg.name} ({dt:.1f} s)"}
 
 
+def run_sweep(elm, torch, steps: int) -> dict:
+    """Study workloads beyond the benchmark configurations (the paper's scalability sweep over the hidden
+    size, its longest-window dataset shape, and prediction on held-out windows), all synthetic."""
+    import dataclasses
+    rows = []
+
+    def timed_fit(cfg, X, T, mode):
+        H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
+        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
+        kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
+                  zero_bias=cfg.zero_bias, contraction=mode, workspace=ws, H_out=H, allow_rank_deficient=True)
+        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)          # warm-up
+        res.model.close()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)
+            st = res.stats
+            res.model.close()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        return {"cell": cfg.cell, "contraction": mode, "N": cfg.N, "Q": cfg.Q, "d": cfg.d, "L": cfg.L,
+                "samples_per_s": cfg.N / dt, "ms_per_fit": 1e3 * dt, "hidden_ms": st.t_hidden_ms,
+                "solve_ms": st.t_solve_ms, "rmse": st.rmse, "rank_deficient": st.rank_deficient}
+
+    def windows(cfg):
+        series = synthdata.make_series(cfg.N + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
+        sd = torch.from_numpy(series).cuda()
+        X = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1))      # zero-copy sliding windows
+        T = sd[cfg.Q:cfg.Q + cfg.N, :cfg.m].contiguous()
+        return X, T
+
+    base = {"elman_diag": synthdata.get_config("paper_elman"),
+            "elman": dataclasses.replace(synthdata.get_config("cfg2"), N=1_000_000, Q=50),
+            "lstm": dataclasses.replace(synthdata.get_config("cfg3"), N=1_000_000, Q=50, d=1),
+            "gru": dataclasses.replace(synthdata.get_config("cfg4"), N=1_000_000, Q=50, d=1, m=1)}
+    for cell, b in base.items():
+        X, T = windows(b)
+        for L in (5, 10, 20, 50, 100):
+            for mode in (("fp32",) if cell == "elman_diag" else ("fp32", "split16")):
+                r = timed_fit(dataclasses.replace(b, L=L), X, T, mode)
+                r["study"] = "hidden-size sweep"
+                rows.append(r)
+    for cell in ("elman", "lstm", "gru"):
+        b = dataclasses.replace(base[cell], N=4500, Q=3197, L=50)
+        X, T = windows(b)
+        for mode in ("fp32", "split16"):
+            r = timed_fit(b, X, T, mode)
+            r["study"] = "long windows"
+            rows.append(r)
+    # fit on the first 80 % of the windows, predict the last 20 %
+    cfg = synthdata.get_config("cfg3")
+    X, T = windows(cfg)
+    n_tr = int(0.8 * cfg.N)
+    res = elm.fit(cfg.cell, X[:n_tr], T[:n_tr], cfg.L, cfg.seed, w_scale=cfg.w_scale, forget_bias=cfg.forget_bias)
+    Y = elm.predict(res.model, X[n_tr:])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        Y = elm.predict(res.model, X[n_tr:])
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    test_rmse = float(torch.sqrt(torch.mean((Y.double() - T[n_tr:].double()) ** 2)))
+    rows.append({"study": "held-out prediction", "cell": cfg.cell, "N_train": n_tr, "N_test": cfg.N - n_tr,
+                 "Q": cfg.Q, "d": cfg.d, "L": cfg.L, "train_rmse": res.stats.rmse, "test_rmse": test_rmse,
+                 "predict_samples_per_s": (cfg.N - n_tr) / dt})
+    res.model.close()
+    return {"metric": "ELM fit samples/sec (H build + TSQR solve) at 1 GPU, study workloads", "unit": "samples/s",
+            "n_gpus": 1, "steps": steps, "data": "synthetic", "sweep": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +157,11 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
                                                      "workload string then names the reduced N)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, time the study workloads: the hidden-size sweep "
+                         "L = 5..100 (N = 1e6, Q = 50, d = 1) for every cell, the long-window shape "
+                         "(N = 4500, Q = 3197), and a fit on 80 %% / predict on 20 %% split; prints one "
+                         "JSON line with a \"sweep\" list")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE "
                          "counters in rocprofv3 --pmc runs)")
@@ -97,6 +173,10 @@ def main() -> int:
 
     import torch
     import paper_1911_13252_amd as elm
+
+    if args.sweep:
+        print(json.dumps(run_sweep(elm, torch, args.steps)))
+        return 0
 
     cfg = synthdata.get_config(args.config)
     if args.n > 0:

@@ -139,10 +139,13 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
 
 // STAGE > 0: that many of a lane's pending new-h values (those of the first column chunk) wait in
 // spare LDS instead of registers; used by the largest LSTM variants, which otherwise spill.
-template <int CELL, int MS, int NCH, int STAGE>
+// WR > 1 (narrow layers, L <= 64, one column chunk): the four waves share 4/WR column blocks and split
+// the tile's rows into WR groups of 32*MS instead, so that no wave is idle.
+template <int CELL, int MS, int NCH, int STAGE, int WR>
 __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
+    static_assert(WR == 1 || NCH == 1, "rows are split over the waves only when one column chunk exists");
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
-    constexpr int S = 32 * MS;
+    constexpr int S = 32 * MS * WR;
     constexpr int PF = 4;
     constexpr bool TWOPASS = (CELL == ELM_CELL_LSTM) && (NCH >= 3);
     extern __shared__ __align__(16) float lds[];
@@ -150,6 +153,8 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     const int tid = threadIdx.x, lane = tid & 63;
     // wave-uniform values are forced into scalar registers: weight addresses then live in SGPRs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wcol = (WR == 1) ? wave : wave % (4 / WR);          // column block of this wave in a chunk
+    const int rbase = (WR == 1) ? 0 : (wave / (4 / WR)) * 32 * MS;   // first tile row of this wave
     const int L = p.L, R = p.R, d = p.d, KG = p.KG;
     const int64_t row0 = (int64_t)blockIdx.x * S;
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
@@ -160,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
 
     // accumulator element (ms, i) of this lane: sample row, hidden column inside the block
     const int col_in = lane & 31;
-    auto acc_row = [&](int ms, int i) { return ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
+    auto acc_row = [&](int ms, int i) { return rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
 
     // ---- initial contents of the activation operand
     for (int idx = tid; idx < S * R; idx += kThreads) {
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     float hn[NCH][MS][16];     // LSTM/Elman: new h until the old one is dead; GRU: update gate z
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        const int jb = ch * 4 + wave;
+        const int jb = ch * 4 + wcol;
         const int col = jb * 32 + col_in;
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
         if (CELL != ELM_CELL_GRU) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 if (jb < p.nJB) {
                     const unsigned wbase = (unsigned)(jb * KG * G) * 1024u;
                     if (TWOPASS) {
@@ -270,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         // the weight queue of each contraction is filled one phase early (before the
                         // point-wise work of the previous contraction), so the first MFMA never waits
                         const int jn = ((ch + 1 < NCH) && ((ch + 1) * 4 + wave < p.nJB)) ? jb + 4 : wave;
-                        contract_main<2, 4, 0, 3, MS, 6>(acc, bq2, A0, R, wrs, wbase, KG, lane);   // gates i, g
+                        contract_main<2, 4, 0, 3, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KG, lane);   // gates i, g
                         prefetch_weights<2, 4, 1, 1, 6>(bq2, wrs, wbase, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
@@ -280,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                                 acc[0][ms][i] = 0.0f;
                                 acc[1][ms][i] = 0.0f;
                             }
-                        contract_main<2, 4, 1, 1, MS, 6>(acc, bq2, A0, R, wrs, wbase, KG, lane);   // gates f, o
+                        contract_main<2, 4, 1, 1, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KG, lane);   // gates f, o
                         prefetch_weights<2, 4, 0, 3, 6>(bq2, wrs, (unsigned)(jn * KG * G) * 1024u, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                                 for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                        contract<G, G, 0, 1, MS, PF>(acc, A0, R, wrs, wbase, KG, lane);
+                        contract<G, G, 0, 1, MS, PF>(acc, A0 + rbase * R, R, wrs, wbase, KG, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -324,11 +329,11 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             {
                 // lane base address, made opaque per step so that the 32*NCH store addresses are
                 // recomputed here (scalar row offsets) instead of being kept live across the unroll
-                int lane_base = (4 * (lane >> 5)) * R + col_in;
+                int lane_base = (rbase + 4 * (lane >> 5)) * R + col_in;
                 asm volatile("" : "+v"(lane_base));
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
-                    const int jb = ch * 4 + wave;
+                    const int jb = ch * 4 + wcol;
                     const int col = jb * 32 + col_in;
                     if (jb < p.nJB && col < L) {
                         float* dst = A0 + lane_base + jb * 32;
@@ -350,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             // phase 1: update and reset gates from h_{t-1}; stage r*h_{t-1} as the second operand
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 const int col = jb * 32 + col_in;
                 if (jb < p.nJB) {
                     floatx16 acc[2][MS];
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                    contract<2, 3, 0, 1, MS, 4>(acc, A0, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
+                    contract<2, 3, 0, 1, MS, 4>(acc, A0 + rbase * R, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -375,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             // phase 2: candidate from r*h_{t-1}; blend; publish h_t into the first operand
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 const int col = jb * 32 + col_in;
                 if (jb < p.nJB) {
                     floatx16 acc[1][MS];
@@ -383,7 +388,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) acc[0][ms][i] = 0.0f;
-                    contract<1, 3, 2, 1, MS, 4>(acc, A1, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
+                    contract<1, 3, 2, 1, MS, 4>(acc, A1 + rbase * R, R, wrs, (unsigned)(jb * KG * 3) * 1024u, KG, lane);
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -411,7 +416,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     if (CELL == ELM_CELL_LSTM && p.C != nullptr) {
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
-            const int jb = ch * 4 + wave;
+            const int jb = ch * 4 + wcol;
             const int col = jb * 32 + col_in;
             if (jb < p.nJB && col < L) {
 #pragma unroll
@@ -426,9 +431,9 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     }
 }
 
-template <int CELL, int MS, int NCH, int STAGE>
+template <int CELL, int MS, int NCH, int STAGE, int WR = 1>
 hipError_t launch_variant(const HiddenArgs& a, int64_t tiles, size_t lds_bytes, hipStream_t stream) {
-    auto kern = hidden_kernel<CELL, MS, NCH, STAGE>;
+    auto kern = hidden_kernel<CELL, MS, NCH, STAGE, WR>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
@@ -460,6 +465,22 @@ hipError_t launch_nch(int nch, const HiddenArgs& a, int64_t tiles, size_t lds, s
 template <int CELL>
 hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t lds_per_row,
                        size_t lds_max, hipStream_t s) {
+    // narrow layers: one or two column blocks only, so the waves split the rows of a larger tile
+    int wr = (a.nJB == 1) ? 4 : (a.nJB == 2) ? 2 : 1;
+    if (lds_per_row * 32 * ms * wr > lds_max) wr = 1;
+    // fewer tiles than compute units: halve the tile so that twice as many work-groups run
+    if (ms == 2 && (N + 64 * wr - 1) / (64 * wr) < 256) ms = 1;
+    if (wr > 1) {
+        const int Sw = 32 * ms * wr;
+        const int64_t tiles = (N + Sw - 1) / Sw;
+        const size_t lds = lds_per_row * Sw;
+        if (ms == 2) {
+            if (wr == 4) return launch_variant<CELL, 2, 1, 0, 4>(a, tiles, lds, s);
+            return launch_variant<CELL, 2, 1, 0, 2>(a, tiles, lds, s);
+        }
+        if (wr == 4) return launch_variant<CELL, 1, 1, 0, 4>(a, tiles, lds, s);
+        return launch_variant<CELL, 1, 1, 0, 2>(a, tiles, lds, s);
+    }
     const int S = 32 * ms;
     const int64_t tiles = (N + S - 1) / S;
     const size_t lds = lds_per_row * S;

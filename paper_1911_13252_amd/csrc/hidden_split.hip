@@ -259,10 +259,13 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const char* __r
 // chunks (1 .. NCH-2) do not wait in registers either: they are parked in the tile's own rows of H (private to the
 // work-group until the last step, which writes them in place) and read back, all loads in flight at
 // once, when the operand is rebuilt.
-template <int CELL, int MS, int NCH, int STAGE>
+// WR > 1 (narrow layers, L <= 64, one column chunk): the four waves share 4/WR column blocks and split
+// the tile's rows into WR groups of 32*MS instead, so that no wave is idle.
+template <int CELL, int MS, int NCH, int STAGE, int WR>
 __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs p) {
+    static_assert(WR == 1 || NCH == 1, "rows are split over the waves only when one column chunk exists");
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
-    constexpr int S = 32 * MS;
+    constexpr int S = 32 * MS * WR;
     // fragment-queue depth; the widest LSTM variants have 24 matrix instructions per group and
     // the fewest spare registers: three groups in flight cover the L2 latency there
     constexpr int PF = (CELL == ELM_CELL_LSTM && NCH >= 3) ? 3 : 4;
@@ -272,6 +275,8 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     const int tid = threadIdx.x, lane = tid & 63;
     // wave-uniform values are forced into scalar registers: weight addresses then live in SGPRs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wcol = (WR == 1) ? wave : wave % (4 / WR);          // column block of this wave in a chunk
+    const int rbase = (WR == 1) ? 0 : (wave / (4 / WR)) * 32 * MS;   // first tile row of this wave
     const int L = p.L, d = p.d, KGs = p.KGs, stride = p.stride, xoff = p.xoff;
     const float k1 = -1.4426950408889634f * p.inv_scale, k2 = 2.885390081777927f * p.inv_scale;
     const int64_t row0 = (int64_t)blockIdx.x * S;
@@ -347,13 +352,13 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     float hn[NCH][MS][16];     // LSTM/Elman: new h until the old one is dead; GRU: update gate z
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        const int jb = ch * 4 + wave;
+        const int jb = ch * 4 + wcol;
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float v = 0.0f;
-                const int64_t row = row0 + ms * 32 + samp_in;
+                const int64_t row = row0 + rbase + ms * 32 + samp_in;
                 const int col = jb * 32 + acc_unit(i);
                 const float* src = (CELL == ELM_CELL_LSTM) ? p.c0 : (CELL == ELM_CELL_GRU) ? p.h0 : nullptr;
                 if (src != nullptr && row < p.N && col < L) v = src[row * L + col];
@@ -373,13 +378,13 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
 
     // lane part of the operand address of this lane's accumulator elements: row samp_in, first
     // column unit0 of the block; element group (ms, q) adds ms*32*stride + jb*128 + h_col_off(8q)
-    const int lane_base0 = samp_in * stride + unit0 * 2;
+    const int lane_base0 = (rbase + samp_in) * stride + unit0 * 2;
     // the tile's rows of H as a range-checked buffer (rows past N are dropped by the hardware);
     // element group (ms, q) of column block jb sits at hvoff + (ms*32*L + jb*32 + 8q)*4
     const int64_t rows_here = (p.N - row0 < S) ? (p.N - row0) : S;
     const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
         p.H + row0 * L, 0, (int)(rows_here * L * 4), 0x00020000);
-    const unsigned hvoff = (unsigned)(samp_in * L + unit0) * 4u;
+    const unsigned hvoff = (unsigned)((rbase + samp_in) * L + unit0) * 4u;
     // Between steps a full tile keeps the staged values in a packed order instead (value e of
     // thread tid at e*1024 + tid*4: every wave store is one contiguous 256 bytes); the last step and
     // a ragged last tile use the true H layout.  (NCH-2)*MS*16 KB always fit the tile's S*L*4 bytes.
@@ -395,7 +400,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
         if (CELL != ELM_CELL_GRU) {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 if (jb < p.nJB) {
                     const unsigned wbase = (unsigned)(jb * KGs * G) * 2048u;
                     {
@@ -406,7 +411,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                                 for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                        contract<G, G, 0, 1, MS, PF>(acc, A0, stride, xoff, wrs, wbase, KGs, lane);
+                        contract<G, G, 0, 1, MS, PF>(acc, A0 + rbase * stride, stride, xoff, wrs, wbase, KGs, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -445,7 +450,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                 asm volatile("" : "+v"(lane_base));
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
-                    const int jb = ch * 4 + wave;
+                    const int jb = ch * 4 + wcol;
                     if (jb < p.nJB) {
                         char* dst = A0 + lane_base + jb * 128;
                         float v[MS][16];
@@ -478,7 +483,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
             // phase 1: update and reset gates from h_{t-1}; stage r*h_{t-1} as the second operand
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 if (jb < p.nJB) {
                     floatx16 acc[2][MS];
 #pragma unroll
@@ -487,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                             for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                    contract<2, 3, 0, 1, MS, PF>(acc, A0, stride, xoff, wrs, (unsigned)(jb * KGs * 3) * 2048u, KGs, lane);
+                    contract<2, 3, 0, 1, MS, PF>(acc, A0 + rbase * stride, stride, xoff, wrs, (unsigned)(jb * KGs * 3) * 2048u, KGs, lane);
                     char* dst = A1 + lane_base0 + jb * 128;
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
@@ -509,14 +514,14 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
             // phase 2: candidate from r*h_{t-1}; blend; publish h_t into the first operand
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const int jb = ch * 4 + wave;
+                const int jb = ch * 4 + wcol;
                 if (jb < p.nJB) {
                     floatx16 acc[1][MS];
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) acc[0][ms][i] = 0.0f;
-                    contract<1, 3, 2, 1, MS, PF>(acc, A1, stride, xoff, wrs, (unsigned)(jb * KGs * 3) * 2048u, KGs, lane);
+                    contract<1, 3, 2, 1, MS, PF>(acc, A1 + rbase * stride, stride, xoff, wrs, (unsigned)(jb * KGs * 3) * 2048u, KGs, lane);
                     char* dst = A0 + lane_base0 + jb * 128;
 #pragma unroll
                     for (int ms = 0; ms < MS; ++ms)
@@ -544,14 +549,14 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     // ---- H(Q) (and the LSTM cell state) straight from the float32 registers
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
-        const int jb = ch * 4 + wave;
+        const int jb = ch * 4 + wcol;
         if (jb < p.nJB) {
             const bool in_place = GSTAGE && ch >= 1 && ch < NCH - 1;      // H already holds these
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int64_t row = row0 + ms * 32 + samp_in;
+                    const int64_t row = row0 + rbase + ms * 32 + samp_in;
                     const int col = jb * 32 + acc_unit(i);
                     if (row < p.N && col < L) {
                         if (!in_place) {
@@ -567,9 +572,9 @@ __global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs 
     }
 }
 
-template <int CELL, int MS, int NCH, int STAGE>
+template <int CELL, int MS, int NCH, int STAGE, int WR = 1>
 hipError_t launch_variant(const SplitArgs& a, int64_t tiles, size_t lds_bytes, hipStream_t stream) {
-    auto kern = hidden_split_kernel<CELL, MS, NCH, STAGE>;
+    auto kern = hidden_split_kernel<CELL, MS, NCH, STAGE, WR>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
@@ -601,6 +606,22 @@ hipError_t launch_nch(int nch, const SplitArgs& a, int64_t tiles, size_t lds, si
 template <int CELL>
 hipError_t launch_cell(int ms, int nch, const SplitArgs& a, int64_t N, size_t lds_per_row,
                        size_t lds_max, hipStream_t s) {
+    // narrow layers: one or two column blocks only, so the waves split the rows of a larger tile
+    int wr = (a.nJB == 1) ? 4 : (a.nJB == 2) ? 2 : 1;
+    if (lds_per_row * 32 * ms * wr > lds_max) wr = 1;
+    // fewer tiles than compute units: halve the tile so that twice as many work-groups run
+    if (ms == 2 && (N + 64 * wr - 1) / (64 * wr) < 256) ms = 1;
+    if (wr > 1) {
+        const int Sw = 32 * ms * wr;
+        const int64_t tiles = (N + Sw - 1) / Sw;
+        const size_t lds = lds_per_row * Sw;
+        if (ms == 2) {
+            if (wr == 4) return launch_variant<CELL, 2, 1, 0, 4>(a, tiles, lds, s);
+            return launch_variant<CELL, 2, 1, 0, 2>(a, tiles, lds, s);
+        }
+        if (wr == 4) return launch_variant<CELL, 1, 1, 0, 4>(a, tiles, lds, s);
+        return launch_variant<CELL, 1, 1, 0, 2>(a, tiles, lds, s);
+    }
     const int S = 32 * ms;
     const int64_t tiles = (N + S - 1) / S;
     const size_t lds = lds_per_row * S;

@@ -44,6 +44,9 @@ def rand_weights(cell, d, L, seed, scale=None):
 SHAPES = [  # N, Q, d, L  (several tiles, ragged tails, every chunk count, awkward sizes)
     (1, 1, 1, 1), (63, 2, 3, 5), (65, 3, 2, 33), (200, 4, 1, 100), (130, 3, 4, 128),
     (77, 3, 8, 160), (129, 2, 4, 256), (70, 2, 5, 300), (64, 3, 8, 512), (33, 2, 2, 385),
+    # enough tiles to fill the chip, so the launcher keeps 64-row blocks per wave: narrow layers whose
+    # waves split the rows (one and two column blocks), a three-block layer, a ragged last tile
+    (70001, 3, 2, 20), (40001, 3, 1, 50), (20000, 2, 3, 90), (16500, 2, 2, 130),
 ]
 
 
