@@ -255,7 +255,12 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
     for (double& v : U) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
     for (double& v : b) v = (2.0 * rng.uniform() - 1.0) * init->w_scale;
     if (init->spectral_radius > 0.0) {
-        const double rho = spectral_radius(U, L);
+        double rho = 0.0;
+        if (L < 64) {
+            rho = spectral_radius(U, L);        // microseconds on the host
+        } else {
+            ELM_HIP_TRY(spectral_radius_device(U.data(), L, &rho));
+        }
         if (!(rho > 0.0)) return ELM_EINVAL;
         const double f = init->spectral_radius / rho;
         for (double& v : U) v *= f;

@@ -30,6 +30,9 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
                          float* H, float* C, hipStream_t stream);
 
+// Spectral radius of a row-major n x n float64 host matrix, computed on the current device.
+hipError_t spectral_radius_device(const double* A, int n, double* rho_out);
+
 // ---- fast contraction mode (fp16 hi/lo split of the recurrent part, bf16 x 3 split of the input part)
 struct SplitLayout {
     int cell, d, L, G;

@@ -243,3 +243,16 @@ def test_split_mode_argument_errors_and_awkward_weight_ranges(elm):
         model.set_contraction("fp32")          # and back
         assert_h_close(elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy(), ocells.hidden(cell, X, W, U, b))
         model.close()
+
+
+@pytest.mark.parametrize("L", [63, 64, 100, 257, 512])
+def test_spectral_radius_scaling_matches_the_oracle(elm, L):
+    # below 64 columns the radius is computed on the host, from 64 on by the device kernels; the
+    # oracle uses numpy's eigenvalues
+    model = elm.Model.create("elman", 4, 2, L, 1, seed=77 + L, w_scale=1.0, spectral_radius=0.9)
+    _, U, _, _ = model.weights()
+    _, Uo, _ = oweights.draw("elman", 2, L, 77 + L, 1.0, 0.9)
+    assert np.max(np.abs(U.astype(np.float64) - Uo) / np.maximum(np.abs(Uo), 1e-30)) < 2e-7
+    assert np.mean(U != Uo) < 1e-3
+    assert abs(oweights.spectral_radius(U) - 0.9) < 1e-6
+    model.close()
