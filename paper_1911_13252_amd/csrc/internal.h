@@ -65,7 +65,7 @@ struct SolvePlan {
     int L, m, n, np;       // n = L + m columns, np = n rounded up to 32
     int block_rows;        // rows per folded block (64 or 128)
     int levels;            // number of fold launches (level 0 + combine levels)
-    int groups[8];         // work-groups (= R factors produced) per level
+    int groups[12];        // work-groups (= R factors produced) per level
     size_t off_R[2];       // ping-pong R-factor stacks (bytes from workspace base)
     size_t off_part;       // per-work-group partial sums of the residual pass (doubles)
     size_t off_small;      // beta64, gradient, scalars (doubles)

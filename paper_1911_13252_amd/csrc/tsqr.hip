@@ -14,8 +14,9 @@
 //       Y = C_R + V_B^T C_B,  W = T^T Y,  C_R -= W,  C_B -= V_B W
 //     where Y and W never leave the accumulator registers (the MFMA k-slot order is chosen so an
 //     accumulator register can be fed back as a B operand).
-// The R factors of all work-groups are combined by the same kernel applied to the stacked R's
-// (fan-in 4 per level, skipping the panels left of each 64-row slice of a triangular input).
+// The R factors of all work-groups are combined by the same kernel in a binary tree: a work-group
+// starts from a copy of its first R and folds the row slices of the second one into it (skipping the
+// panels left of each slice of the triangular input), so a level costs one R fold of serial work.
 
 #include "internal.h"
 
@@ -26,7 +27,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int kNB = 32;         // panel width = MFMA tile width
-constexpr int kFan = 4;         // R factors folded by one work-group in a combine level
+constexpr int kFan = 2;         // R factors merged by one work-group in a combine level
 
 struct FoldArgs {
     const float* src0;   // level 0: H (ld = nc0 = L); combine: previous R stack (ld = nc0 = np)
@@ -44,6 +45,13 @@ struct FoldArgs {
 // value of x in lane `src` (compile-time constant), delivered through a scalar register
 __device__ __forceinline__ float lane_bcast(float x, int src) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src));
+}
+
+// value of x in the lane 32 positions away (the other half of the wavefront), without an LDS round trip
+__device__ __forceinline__ float other_half(float x, int half) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, half ? r[0] : r[1]);
 }
 
 // row index inside a 32x32 accumulator tile held in register q by a lane of half h
@@ -73,18 +81,19 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
     const int half = lane >> 5;
     float* R = a.Rout + (size_t)blockIdx.x * np * np;
 
-    for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
-
-    // ---- which blocks does this work-group fold?
+    // ---- which blocks does this work-group fold, and what does its R start from?
     int blk_begin, blk_end, per_r = 1;
     if (!a.combine) {
+        for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
         blk_begin = (int)(((int64_t)a.nblocks * blockIdx.x) / gridDim.x);
         blk_end = (int)(((int64_t)a.nblocks * (blockIdx.x + 1)) / gridDim.x);
     } else {
         per_r = (np + BR - 1) / BR;                           // BR-row slices per R factor
         const int r_begin = blockIdx.x * kFan;
         const int r_end = min(r_begin + kFan, a.nprev);
-        blk_begin = r_begin * per_r;
+        const float* first = a.src0 + (size_t)r_begin * np * np;
+        for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = first[idx];
+        blk_begin = (r_begin + 1) * per_r;
         blk_end = r_end * per_r;
     }
     __syncthreads();
@@ -143,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
                     xk[i] = half ? hi : lo;
                     s = fmaf(xk[i], pv[i], s);
                 }
-                s += __shfl_xor(s, 32);
+                s += other_half(s, half);
                 float* rb = red + (k & 1) * 128;
                 if (half == 0) rb[wave * 32 + j] = s;
                 const float x0 = lane_bcast(rdv[k], k);     // every copy is identical
