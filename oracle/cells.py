@@ -119,7 +119,34 @@ def hidden_elman_diag(X, W, alpha, b, steps=None):
     return hist[steps] if steps > 0 else np.zeros((N, L))
 
 
-GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
+def hidden_fc_multilag(X, W, A, b, steps=None):
+    """The paper's fully connected cell (section "Fully Connected RNN", Eq. hij_fc): every neuron is fed
+    by every neuron's output of all earlier steps of the window.
+
+    h(t) = tanh( x(t) W + b + sum_{k=1}^{t-1} h(t-k) A[k-1] ),   t = 1..steps,
+    with A of shape [Q, L, L] (A[k-1][m, j] weighs neuron m's output of k steps ago into neuron j) and
+    no state before t = 1; as for the Elman cell, g is applied, the bias is per neuron and only strictly
+    earlier steps feed back, so A[Q-1] is never used.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    N, Q, d = X.shape
+    L = W.shape[1]
+    steps = Q if steps is None else int(steps)
+    if not 0 <= steps <= Q or A.shape != (Q, L, L):
+        raise ValueError("A must be [Q, L, L] and steps must lie in [0, Q]")
+    hist = np.zeros((steps + 1, N, L))           # hist[t] = h(t), hist[0] unused (no state before t = 1)
+    for t in range(1, steps + 1):
+        a = X[:, t - 1, :] @ W + b
+        for k in range(1, t):
+            a = a + hist[t - k] @ A[k - 1]
+        hist[t] = np.tanh(a)
+    return hist[steps] if steps > 0 else np.zeros((N, L))
+
+
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1, "fc_multilag": 1}
 
 
 def hidden(cell: str, X, W, U, b, h0=None, c0=None, steps=None):
@@ -134,13 +161,17 @@ def hidden(cell: str, X, W, U, b, h0=None, c0=None, steps=None):
         if h0 is not None:
             raise ValueError("the multi-lag cell has no single initial state")
         return hidden_elman_diag(X, W, U, b, steps=steps)
+    if cell == "fc_multilag":
+        if h0 is not None:
+            raise ValueError("the multi-lag cell has no single initial state")
+        return hidden_fc_multilag(X, W, U, b, steps=steps)
     raise ValueError(f"unknown cell {cell!r}")
 
 
 def hidden_chunked(cell: str, X, W, U, b, chunk: int = 8192, **kw):
     """Same as hidden() but over row chunks (rows are independent), for large N."""
     N = X.shape[0]
-    L = np.asarray(U).shape[0]
+    L = np.asarray(W).shape[1] // GATES[cell]
     out = np.empty((N, L), dtype=np.float64)
     for s in range(0, N, chunk):
         e = min(N, s + chunk)

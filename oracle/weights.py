@@ -19,7 +19,7 @@ from __future__ import annotations
 
 import numpy as np
 
-GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1, "fc_multilag": 1}
 
 _GAMMA = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
@@ -51,18 +51,20 @@ def draw(cell: str, d: int, L: int, seed: int, w_scale: float = 1.0,
     """Return (W [d,kL], U [L,kL], b [kL]) as float32 arrays.
 
     For the paper's own Elman cell ("elman_diag") the recurrent weights are alpha [L, Q] (lag k in
-    column k-1), drawn in the same place of the stream as U.
+    column k-1), for its fully connected cell ("fc_multilag") A [Q, L, L] (lag k in block k-1), both
+    drawn in the same place of the stream as U.
     """
     k = GATES[cell]
     kL = k * L
-    ucols = Q if cell == "elman_diag" else kL
-    if cell == "elman_diag" and Q < 1:
-        raise ValueError("the multi-lag cell needs Q")
-    n = d * kL + L * ucols + kL
+    ushape = (L, Q) if cell == "elman_diag" else (Q, L, L) if cell == "fc_multilag" else (L, kL)
+    if cell in ("elman_diag", "fc_multilag") and Q < 1:
+        raise ValueError("the multi-lag cells need Q")
+    nu = int(np.prod(ushape))
+    n = d * kL + nu + kL
     v = (2.0 * uniform01(seed, n) - 1.0) * float(w_scale)
     W = v[:d * kL].reshape(d, kL)
-    U = v[d * kL:d * kL + L * ucols].reshape(L, ucols)
-    b = v[d * kL + L * ucols:].copy()
+    U = v[d * kL:d * kL + nu].reshape(ushape)
+    b = v[d * kL + nu:].copy()
     if spectral_radius_target > 0.0:
         if cell != "elman":
             raise ValueError("spectral-radius scaling is defined for the Elman cell only")

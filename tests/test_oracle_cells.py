@@ -310,3 +310,54 @@ def test_elman_diag_brute_force_from_the_equation():
     got2 = cells.hidden_elman_diag(X, W, alpha2, b)
     assert np.abs(got2[:, 2] - got[:, 2]).max() > 1e-3
     np.testing.assert_array_equal(np.delete(got2, 2, axis=1), np.delete(got, 2, axis=1))
+
+
+# ----------------------------------------------------------------- the paper's fully connected (dense, multi-lag) cell
+
+def test_fc_multilag_with_lag_one_only_is_the_dense_elman_cell():
+    N, Q, d, L = 6, 5, 2, 4
+    X, W, b = rnd((N, Q, d), 90), rnd((d, L), 91), rnd(L, 92)
+    A = np.zeros((Q, L, L))
+    A[0] = rnd((L, L), 93)
+    np.testing.assert_allclose(cells.hidden_fc_multilag(X, W, A, b), cells.hidden_elman(X, W, A[0], b), atol=1e-15)
+    # no feedback at all, or a single step: the feed-forward ELM layer
+    np.testing.assert_allclose(cells.hidden_fc_multilag(X, W, np.zeros((Q, L, L)), b),
+                               np.tanh(X[:, Q - 1, :] @ W + b), atol=1e-15)
+    np.testing.assert_allclose(cells.hidden_fc_multilag(X[:, :1], W, rnd((1, L, L), 94), b),
+                               np.tanh(X[:, 0, :] @ W + b), atol=1e-15)
+
+
+def test_fc_multilag_with_diagonal_lag_matrices_is_the_papers_elman_cell():
+    N, Q, d, L = 5, 6, 3, 4
+    X, W, b = rnd((N, Q, d), 95), rnd((d, L), 96), rnd(L, 97)
+    alpha = rnd((L, Q), 98)
+    A = np.stack([np.diag(alpha[:, k]) for k in range(Q)])
+    np.testing.assert_allclose(cells.hidden_fc_multilag(X, W, A, b), cells.hidden_elman_diag(X, W, alpha, b),
+                               atol=1e-15)
+
+
+def test_fc_multilag_brute_force_from_the_equation():
+    N, Q, d, L = 2, 4, 2, 3
+    X, W, A, b = rnd((N, Q, d), 99), rnd((d, L), 100), rnd((Q, L, L), 101), rnd(L, 102)
+    ref = np.zeros((N, L))
+    for i in range(N):
+        h = {}
+        for t in range(1, Q + 1):
+            h[t] = [0.0] * L
+            for j in range(L):
+                a = sum(W[s][j] * X[i, t - 1, s] for s in range(d)) + b[j]
+                for k in range(1, t):
+                    a += sum(A[k - 1][m][j] * h[t - k][m] for m in range(L))
+                h[t][j] = math.tanh(a)
+        ref[i] = h[Q]
+    got = cells.hidden_fc_multilag(X, W, A, b)
+    np.testing.assert_allclose(got, ref, atol=1e-14)
+    # the last lag block is never used; a transposed lag matrix is a different network
+    A2 = A.copy()
+    A2[Q - 1] += 1.0
+    np.testing.assert_array_equal(cells.hidden_fc_multilag(X, W, A2, b), got)
+    A3 = A.copy()
+    A3[1] = A3[1].T
+    assert np.abs(cells.hidden_fc_multilag(X, W, A3, b) - got).max() > 1e-3
+    np.testing.assert_allclose(cells.hidden_fc_multilag(X, W, A, b, steps=2),
+                               np.tanh(X[:, 1] @ W + b + np.tanh(X[:, 0] @ W + b) @ A[0]), atol=1e-15)
