@@ -29,7 +29,8 @@
  *   - Weight layout: W is d x kL, U is L x kL, b is kL with k gate blocks side
  *     by side: Elman k = 1; LSTM k = 4 in the order (i, f, o, g) = the paper's
  *     (in, lambda, o, candidate); GRU k = 3 in the order (z, r, n).  For
- *     ELM_CELL_ELMAN_DIAG k = 1 and U is the L x Q lag-weight matrix alpha.
+ *     ELM_CELL_ELMAN_DIAG k = 1 and U is the L x Q lag-weight matrix alpha; for
+ *     ELM_CELL_FC_MULTILAG k = 1 and U is the Q x L x L stack of lag matrices.
  *   - Supported sizes: 1 <= L <= 512, 1 <= d <= 64, 1 <= m <= 16, N >= 1.
  */
 #ifndef ELM_RNN_H
@@ -52,6 +53,13 @@ extern "C" {
                                 h_j(t) = tanh(x(t) W[:,j] + b_j + sum_{k=1}^{t-1} alpha[j][k-1] h_j(t-k));
                                 its recurrent array "U" is alpha, L x Q (lag k in column k-1), Q <= 512;
                                 no initial state can be passed and Q_run <= Q                        */
+
+#define ELM_CELL_FC_MULTILAG 4 /* the paper's section "Fully Connected RNN" (Eq. hij_fc): every neuron is fed
+                                by every neuron's output of all earlier steps of the window:
+                                h(t) = tanh(x(t) W + b + sum_{k=1}^{t-1} h(t-k) A_k);
+                                its recurrent array "U" is A, Q x L x L (A[k-1][m][j]: neuron m, k steps
+                                ago, into neuron j; the last block is never used); needs
+                                max(Q-1,1)*L + d + 1 <= 1272; no initial state, Q_run <= Q          */
 
 /* How the dense cells carry the recurrent contraction h_{t-1} U of each step (the input part x_t W + b
  * and all point-wise work are float32-exact in both):
@@ -112,7 +120,7 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
                          const elm_rnn_init* init, elm_rnn_model** model_out);
 
 /* Same, but with caller-supplied float32 host weights W[d*kL], U[L*kL] (alpha[L*Q] for
- * ELM_CELL_ELMAN_DIAG), b[kL] (copied). */
+ * ELM_CELL_ELMAN_DIAG, A[Q*L*L] for ELM_CELL_FC_MULTILAG), b[kL] (copied). */
 int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m,
                                       const float* W, const float* U, const float* b,
                                       elm_rnn_model** model_out);

@@ -8,8 +8,8 @@ from typing import Optional
 
 import numpy as np
 
-CELLS = {"elman": 0, "lstm": 1, "gru": 2, "elman_diag": 3}
-GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
+CELLS = {"elman": 0, "lstm": 1, "gru": 2, "elman_diag": 3, "fc_multilag": 4}
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1, "fc_multilag": 1}
 
 ELM_OK, ELM_EINVAL, ELM_EWORKSPACE, ELM_ERANK, ELM_EHIP, ELM_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
@@ -162,15 +162,16 @@ class Model:
     @classmethod
     def from_weights(cls, cell: str, Q: int, m: int, W, U, b) -> "Model":
         """elm_rnn_model_create_from_weights with host float32 arrays W [d,kL], U [L,kL], b [kL]
-        (for "elman_diag" U is the lag-weight matrix alpha [L, Q])."""
+        (for "elman_diag" U is the lag-weight matrix alpha [L, Q], for "fc_multilag" the stack of lag
+        matrices A [Q, L, L])."""
         lib = load_library()
         W = np.ascontiguousarray(W, dtype=np.float32)
         U = np.ascontiguousarray(U, dtype=np.float32)
         b = np.ascontiguousarray(b, dtype=np.float32)
         k = GATES[cell]
-        L, d = U.shape[0], W.shape[0]
-        ucols = Q if cell == "elman_diag" else k * L
-        if U.shape != (L, ucols) or W.shape != (d, k * L) or b.shape != (k * L,):
+        d, L = W.shape[0], W.shape[1] // k
+        ushape = (L, Q) if cell == "elman_diag" else (Q, L, L) if cell == "fc_multilag" else (L, k * L)
+        if U.shape != ushape or W.shape != (d, k * L) or b.shape != (k * L,):
             raise ValueError("weight shapes do not match the cell")
         out = C.c_void_p()
         _check(lib.elm_rnn_model_create_from_weights(CELLS[cell], Q, d, L, m, W.ctypes.data, U.ctypes.data,
@@ -182,7 +183,9 @@ class Model:
         lib = load_library()
         k = GATES[self.cell]
         W = np.empty((self.d, k * self.L), np.float32)
-        U = np.empty((self.L, self.Q if self.cell == "elman_diag" else k * self.L), np.float32)
+        ushape = ((self.L, self.Q) if self.cell == "elman_diag" else
+                  (self.Q, self.L, self.L) if self.cell == "fc_multilag" else (self.L, k * self.L))
+        U = np.empty(ushape, np.float32)
         b = np.empty(k * self.L, np.float32)
         beta = np.empty((self.L, self.m), np.float64)
         _check(lib.elm_rnn_get_weights(self._h, W.ctypes.data, U.ctypes.data, b.ctypes.data, beta.ctypes.data))

@@ -94,19 +94,26 @@ double spectral_radius(const std::vector<double>& A, int n) {
     return std::exp(log_rho);
 }
 
+// history slots of the fully connected multi-lag cell: lags 1 .. Q-1 can occur inside a window
+int fc_ring(int Q) { return Q > 1 ? Q - 1 : 1; }
+
 int check_dims(int cell, int Q, int d, int L, int m) {
     if (cell != ELM_CELL_ELMAN && cell != ELM_CELL_LSTM && cell != ELM_CELL_GRU &&
-        cell != ELM_CELL_ELMAN_DIAG)
+        cell != ELM_CELL_ELMAN_DIAG && cell != ELM_CELL_FC_MULTILAG)
         return ELM_EINVAL;
     if (Q < 1 || d < 1 || L < 1 || m < 1) return ELM_EINVAL;
     if (L > 512 || d > 64 || m > 16) return ELM_EUNSUPPORTED;
     if (cell == ELM_CELL_ELMAN_DIAG && Q > kDiagMaxQ) return ELM_EUNSUPPORTED;
+    if (cell == ELM_CELL_FC_MULTILAG && (int64_t)fc_ring(Q) * L + d + 1 > kFcMaxK) return ELM_EUNSUPPORTED;
     return ELM_OK;
 }
 
-// columns of the recurrent weight array: k*L for the dense cells, Q lags for the diagonal cell
+// columns per row of the recurrent weight array: k*L for the dense lag-1 cells, Q lags for the
+// diagonal cell, Q blocks of L for the fully connected multi-lag cell (stored [Q][L][L])
 size_t recurrent_cols(int cell, int Q, int L) {
-    return cell == ELM_CELL_ELMAN_DIAG ? (size_t)Q : (size_t)gates_of(cell) * L;
+    if (cell == ELM_CELL_ELMAN_DIAG) return (size_t)Q;
+    if (cell == ELM_CELL_FC_MULTILAG) return (size_t)Q * L;
+    return (size_t)gates_of(cell) * L;
 }
 
 int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, std::vector<float>&& U,
@@ -125,6 +132,10 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         std::copy(mdl->U.begin(), mdl->U.end(), packed.begin() + (size_t)L * d);
         std::copy(mdl->b.begin(), mdl->b.end(), packed.begin() + (size_t)L * d + (size_t)L * Q);
         dst = &mdl->dDiag;
+    } else if (cell == ELM_CELL_FC_MULTILAG) {
+        mdl->lay = packed_layout(cell, d, L, fc_ring(Q));
+        packed.resize(mdl->lay.floats);
+        pack_weights_fc(mdl->lay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
     } else {
         mdl->lay = packed_layout(cell, d, L);
         packed.resize(mdl->lay.floats);
@@ -148,7 +159,7 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
 // cannot use the mode.
 int enable_split(elm_rnn_model* mdl) {
     if (mdl->dWs != nullptr) return ELM_OK;
-    if (mdl->cell == ELM_CELL_ELMAN_DIAG) return ELM_EUNSUPPORTED;
+    if (mdl->cell == ELM_CELL_ELMAN_DIAG || mdl->cell == ELM_CELL_FC_MULTILAG) return ELM_EUNSUPPORTED;
     mdl->slay = split_layout(mdl->cell, mdl->d, mdl->L, mdl->W.data(), mdl->U.data(), mdl->b.data());
     if (!mdl->slay.ok) return ELM_EUNSUPPORTED;
     std::vector<unsigned char> packed(mdl->slay.bytes);
@@ -337,8 +348,8 @@ int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, in
                    float* c_out, void* hip_stream) {
     if (model == nullptr || X == nullptr || H_out == nullptr) return ELM_EINVAL;
     if (N < 1 || Q_run < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
-    if (model->cell == ELM_CELL_ELMAN_DIAG && (h0 != nullptr || c0 != nullptr || c_out != nullptr ||
-                                               Q_run > model->Q))
+    if ((model->cell == ELM_CELL_ELMAN_DIAG || model->cell == ELM_CELL_FC_MULTILAG) &&
+        (h0 != nullptr || c0 != nullptr || c_out != nullptr || Q_run > model->Q))
         return ELM_EINVAL;
     ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out,
                            static_cast<hipStream_t>(hip_stream)));

@@ -42,6 +42,8 @@ struct HiddenArgs {
     int64_t N;
     int Q_run, d, L, R, KG, nJB;
     unsigned wp_bytes;
+    int ring;              // history slots in the operand row (1; Q-1 for the fully connected multi-lag cell)
+    unsigned copy_bytes;   // distance between the per-step rotations of the packed weights (ring > 1)
 };
 
 __device__ __forceinline__ float sigmoid_f(float x) {
@@ -168,17 +170,21 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     auto acc_row = [&](int ms, int i) { return rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
 
     // ---- initial contents of the activation operand
+    // The operand row is [history | x_t | 1 | 0...]: one slot of L columns (h_{t-1}) for the lag-1
+    // cells; for the fully connected multi-lag cell a ring of p.ring slots, h(t') in slot (t'-1) % ring,
+    // read with the weights rotated accordingly (copy t % ring of the packed operand at step t).
+    const int xcol = p.ring * L;                   // first input column
     for (int idx = tid; idx < S * R; idx += kThreads) {
         const int s = idx / R, k = idx - s * R;
         const int64_t row = row0 + s;
         float v = 0.0f;
         if (k < L) {
             if (p.h0 != nullptr && row < p.N) v = p.h0[row * L + k];
-        } else if (k == L + d) {
+        } else if (k == xcol + d) {
             v = 1.0f;
         }
         A0[idx] = v;
-        if (CELL == ELM_CELL_GRU) A1[idx] = (k == L + d) ? 1.0f : 0.0f;
+        if (CELL == ELM_CELL_GRU) A1[idx] = (k == xcol + d) ? 1.0f : 0.0f;
     }
 
     const int nx = S * d;                          // input values per step for this tile
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             const int e = tid + q * kThreads;
             if (e < nx) {
                 const int s = e / d, dd = e - s * d;
-                buf[s * R + L + dd] = xr[q];
+                buf[s * R + xcol + dd] = xr[q];
             }
         }
     };
@@ -210,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
         for (int e = tid; e < nx; e += kThreads) {
             const int s = e / d, dd = e - s * d;
             const int64_t row = row0 + s;
-            buf[s * R + L + dd] =
+            buf[s * R + xcol + dd] =
                 (row < p.N) ? p.X[row * p.ldx_n + (int64_t)t * p.ldx_q + dd] : 0.0f;
         }
     };
@@ -248,11 +254,13 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     if (TWOPASS && wave < p.nJB)
         prefetch_weights<2, 4, 0, 3, 6>(bq2, wrs, (unsigned)(wave * KG * G) * 1024u, lane);
 
+    int slot = 0;                  // t % ring: weight rotation of this step and slot that receives h(t+1)
     for (int t = 0; t < p.Q_run; ++t) {
         if (CELL == ELM_CELL_GRU) {
             if (x_prefetch) store_x(A1); else copy_x_direct(t, A1);
         }
         const bool more = (t + 1 < p.Q_run);
+        const unsigned wrot = (unsigned)slot * p.copy_bytes;
         if (x_prefetch && more) load_x(t + 1);
 
         if (CELL != ELM_CELL_GRU) {
@@ -260,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             for (int ch = 0; ch < NCH; ++ch) {
                 const int jb = ch * 4 + wcol;
                 if (jb < p.nJB) {
-                    const unsigned wbase = (unsigned)(jb * KG * G) * 1024u;
+                    const unsigned wbase = (unsigned)(jb * KG * G) * 1024u + wrot;
                     if (TWOPASS) {
                         // LSTM with many column chunks: two contractions of two gates each keep the
                         // accumulators at 64 registers so that c and the pending h stay in registers
@@ -336,7 +344,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                     const int jb = ch * 4 + wcol;
                     const int col = jb * 32 + col_in;
                     if (jb < p.nJB && col < L) {
-                        float* dst = A0 + lane_base + jb * 32;
+                        float* dst = A0 + lane_base + slot * L + jb * 32;
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -349,6 +357,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             }
             if (more) {
                 if (x_prefetch) store_x(A0); else copy_x_direct(t + 1, A0);
+                slot = (slot + 1 == p.ring) ? 0 : slot + 1;
             }
             __syncthreads();
         } else {
@@ -411,7 +420,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     for (int idx = tid; idx < S * L; idx += kThreads) {
         const int s = idx / L, j = idx - s * L;
         const int64_t row = row0 + s;
-        if (row < p.N) p.H[row * L + j] = A0[s * R + j];
+        if (row < p.N) p.H[row * L + j] = A0[s * R + slot * L + j];
     }
     if (CELL == ELM_CELL_LSTM && p.C != nullptr) {
 #pragma unroll
@@ -490,19 +499,51 @@ hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t l
 
 }  // namespace
 
-PackedLayout packed_layout(int cell, int d, int L) {
+PackedLayout packed_layout(int cell, int d, int L, int ring) {
     PackedLayout lay{};
     lay.cell = cell;
     lay.d = d;
     lay.L = L;
     lay.G = gates_of(cell);
-    lay.K = L + d + 1;
+    lay.ring = ring;
+    lay.K = ring * L + d + 1;
     lay.KG = (lay.K + 7) / 8;
     lay.R = 8 * lay.KG + 4;
     lay.nJB = (L + 31) / 32;
     // 4 extra k-groups: the contraction's look-ahead loads read (harmlessly) past the last group
-    lay.floats = ((size_t)lay.nJB * lay.KG + 4) * lay.G * 256;
+    lay.copy_floats = ((size_t)lay.nJB * lay.KG + 4) * lay.G * 256;
+    lay.floats = lay.copy_floats * ring;
     return lay;
+}
+
+// Fully connected multi-lag cell: `ring` rotations of the packed operand [A_k(0); A_k(1); ...; W; b].
+// Rotation c is used at the steps t with t % ring == c, when history slot s holds the state of
+// 1 + (c - 1 - s) mod ring steps ago; A is [Q][L][L] (lag k in block k-1).
+void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, const float* b, float* out) {
+    const int L = lay.L, d = lay.d, ring = lay.ring;
+    for (size_t i = 0; i < lay.floats; ++i) out[i] = 0.0f;
+    for (int c = 0; c < ring; ++c) {
+        float* oc = out + (size_t)c * lay.copy_floats;
+        for (int jb = 0; jb < lay.nJB; ++jb)
+            for (int kg = 0; kg < lay.KG; ++kg)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 4; ++e) {
+                        const int k = kg * 8 + (lane >> 5) * 4 + e;
+                        const int j = jb * 32 + (lane & 31);
+                        if (k >= lay.K || j >= L) continue;
+                        float v;
+                        if (k < ring * L) {
+                            const int s = k / L, m = k - s * L;
+                            const int lag = 1 + (((c - 1 - s) % ring) + ring) % ring;
+                            v = A[((size_t)(lag - 1) * L + m) * L + j];
+                        } else if (k < ring * L + d) {
+                            v = W[(size_t)(k - ring * L) * L + j];
+                        } else {
+                            v = b[j];
+                        }
+                        oc[(((size_t)jb * lay.KG + kg) * 64 + lane) * 4 + e] = v;
+                    }
+    }
 }
 
 void pack_weights(const PackedLayout& lay, const float* W, const float* U, const float* b, float* out) {
@@ -545,8 +586,11 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
     a.X = X; a.ldx_n = ldx_n; a.ldx_q = ldx_q; a.Wp = Wp; a.h0 = h0; a.c0 = c0;
     a.H = H; a.C = C; a.N = N; a.Q_run = Q_run; a.d = lay.d; a.L = lay.L; a.R = lay.R;
     a.KG = lay.KG; a.nJB = lay.nJB; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
+    a.ring = lay.ring; a.copy_bytes = (unsigned)(lay.copy_floats * sizeof(float));
     switch (lay.cell) {
-        case ELM_CELL_ELMAN: return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
+        case ELM_CELL_ELMAN:
+        case ELM_CELL_FC_MULTILAG:      // the Elman update on a ring of history slots
+            return launch_cell<ELM_CELL_ELMAN>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
         case ELM_CELL_LSTM:  return launch_cell<ELM_CELL_LSTM>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
         case ELM_CELL_GRU:   return launch_cell<ELM_CELL_GRU>(ms, nch, a, N, lds_per_row, (size_t)lds_max, stream);
         default: return hipErrorInvalidValue;

@@ -13,18 +13,23 @@ namespace elm {
 // Geometry of the packed weight operand [U; W; b] (K x G*L) as the hidden-matrix kernel reads it.
 struct PackedLayout {
     int cell, d, L, G;
-    int K;        // L + d + 1 contraction rows: recurrent, input, bias
+    int ring;     // history slots of L columns in the operand row (1 except for the fully connected multi-lag cell)
+    int K;        // ring*L + d + 1 contraction rows: recurrent, input, bias
     int KG;       // k-groups of 8 rows (ceil(K / 8))
     int R;        // LDS row stride of the activation operand, 8*KG + 4 floats
     int nJB;      // hidden-unit blocks of 32 columns (ceil(L / 32))
-    size_t floats;   // packed buffer length including the prefetch tail
+    size_t copy_floats;   // one packed operand including the prefetch tail
+    size_t floats;        // whole buffer: `ring` rotations of the operand
 };
 
 inline int gates_of(int cell) { return cell == ELM_CELL_LSTM ? 4 : cell == ELM_CELL_GRU ? 3 : 1; }
-PackedLayout packed_layout(int cell, int d, int L);
+PackedLayout packed_layout(int cell, int d, int L, int ring = 1);
 
 // Pack host W (d x GL), U (L x GL), b (GL) into the kernel's fragment order.
 void pack_weights(const PackedLayout& lay, const float* W, const float* U, const float* b, float* out);
+// Same for the fully connected multi-lag cell: A is [Q][L][L], lay.ring rotations are written.
+void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, const float* b, float* out);
+constexpr int kFcMaxK = 1272;      // contraction rows a 32-sample tile of the multi-lag cell can hold in LDS
 
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
