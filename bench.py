@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 
 import synthdata  # noqa: E402
 
-GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1}
+GATES = {"elman": 1, "lstm": 4, "gru": 3, "elman_diag": 1, "fc_multilag": 1}
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
 PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
 PEAK_FP32_VECTOR_TFLOPS = 157.3   # MI355X fp32 vector peak (256 CUs x 4 SIMDs x 32 FMA lanes-equivalent x 2.4 GHz)
@@ -45,9 +45,12 @@ MEASURED_TRAFFIC_SPLIT_BYTES = {"cfg5": 1283.1e9 + 413.7e9}   # profiles/fit_cfg
 
 def stage1_flops(cfg) -> float:
     """Algorithmic flops of one hidden-matrix launch: 2 Q kL (L + d) per sample for the dense cells,
-    2 L (Q (Q - 1) / 2 + Q d) for the paper's diagonal multi-lag Elman."""
+    2 L (Q (Q - 1) / 2 + Q d) for the paper's diagonal multi-lag Elman, 2 L (L Q (Q - 1) / 2 + Q d) for
+    its fully connected multi-lag cell."""
     if cfg.cell == "elman_diag":
         return 2.0 * cfg.L * (cfg.Q * (cfg.Q - 1) / 2 + cfg.Q * cfg.d) * cfg.N
+    if cfg.cell == "fc_multilag":      # step t contracts (t - 1) L + d columns
+        return 2.0 * cfg.L * (cfg.L * cfg.Q * (cfg.Q - 1) / 2 + cfg.Q * cfg.d) * cfg.N
     return 2.0 * cfg.Q * GATES[cfg.cell] * cfg.L * (cfg.L + cfg.d) * cfg.N
 
 
@@ -206,10 +209,11 @@ def main() -> int:
                     "kernel": "diag_reg_kernel / diag_lds_kernel (stage 1, fp32 vector FMA; the build "
                               "disables packed fp32, which caps the rate at half the published peak)"}
         if mode == "fp32":
-            return {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                    "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"}
+            r = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                 "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                 "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"}
+            return r
         # three fp16 matrix instructions per algorithmic product (hi*hi, hi*lo, lo*hi): the
         # algorithmic rate can reach at most a third of the fp16 peak
         return {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_MFMA_TFLOPS,
@@ -259,7 +263,8 @@ def main() -> int:
                    "rmse": stats[-1].rmse, "ne_resid": stats[-1].ne_resid},
         "roofline": roofline(args.contraction, hidden_ms),
     }
-    if not args.no_fast_mode and args.contraction == "fp32" and cfg.d <= 15 and cfg.cell != "elman_diag":
+    if (not args.no_fast_mode and args.contraction == "fp32" and cfg.d <= 15
+            and cfg.cell in ("elman", "lstm", "gru")):
         step("split16")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -274,7 +279,7 @@ def main() -> int:
                             "roofline": roofline("split16", f_hidden)}
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
-                                 "cfg5": 4096, "paper_elman": 20_000}[cfg.name]
+                                 "cfg5": 4096, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]
         out["cpu_baseline"] = cpu_baseline(cfg, rows)
     print(json.dumps(out))
     return 0

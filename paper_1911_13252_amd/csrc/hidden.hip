@@ -1,9 +1,9 @@
 // Stage 1: the hidden-matrix build H(Q) (step 2 of the paper's Algorithm "S-R-ELM").
 //
 // One work-group owns a tile of S = 32*MS windows for all Q steps.  Per step it evaluates the
-// gate pre-activations  A_t = [h_{t-1} | x_t | 1] . [U; W; b]  as a dense fp32 MFMA contraction
+// gate pre-activations  A_t = [x_t | 1 | h_{t-1}] . [W; b; U]  as a dense fp32 MFMA contraction
 // (samples x K) . (K x G*L), then the cell's point-wise update (the paper's sections "Elman",
-// "LSTM", "GRU").  The activation operand [h | x | 1] lives in LDS for the whole unroll, the cell
+// "LSTM", "GRU").  The activation operand [x | 1 | h] lives in LDS for the whole unroll, the cell
 // state c (and the freshly computed h until every wave has finished reading the old one) lives
 // in registers, the weights stream from L2 in a pre-packed fragment order.  HBM is read once per
 // window element and written once per H row.
@@ -161,8 +161,8 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     const int64_t row0 = (int64_t)blockIdx.x * S;
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
-    float* A0 = lds;               // [S][R]: h_{t-1} | x_t | 1 | 0...
-    float* A1 = lds + S * R;       // GRU only: (r*h_{t-1}) | x_t | 1 | 0...
+    float* A0 = lds;               // [S][R]: x_t | 1 | h_{t-1} | 0...
+    float* A1 = lds + S * R;       // GRU only: x_t | 1 | (r*h_{t-1}) | 0...
     float* stage = lds + S * R + tid;   // STAGE > 0: [STAGE][256] behind the operand, one column per thread
 
     // accumulator element (ms, i) of this lane: sample row, hidden column inside the block
@@ -170,21 +170,22 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     auto acc_row = [&](int ms, int i) { return rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); };
 
     // ---- initial contents of the activation operand
-    // The operand row is [history | x_t | 1 | 0...]: one slot of L columns (h_{t-1}) for the lag-1
+    // The operand row is [x_t | 1 | history | 0...]: one slot of L columns (h_{t-1}) for the lag-1
     // cells; for the fully connected multi-lag cell a ring of p.ring slots, h(t') in slot (t'-1) % ring,
-    // read with the weights rotated accordingly (copy t % ring of the packed operand at step t).
-    const int xcol = p.ring * L;                   // first input column
+    // read with the weights rotated accordingly (copy t % ring of the packed operand at step t).  The
+    // history comes last so that the slots not yet written (all zero) are a tail the contraction skips.
+    const int hoff = d + 1;                        // first history column
     for (int idx = tid; idx < S * R; idx += kThreads) {
         const int s = idx / R, k = idx - s * R;
         const int64_t row = row0 + s;
         float v = 0.0f;
-        if (k < L) {
-            if (p.h0 != nullptr && row < p.N) v = p.h0[row * L + k];
-        } else if (k == xcol + d) {
+        if (k >= hoff && k < hoff + L) {
+            if (p.h0 != nullptr && row < p.N) v = p.h0[row * L + (k - hoff)];
+        } else if (k == d) {
             v = 1.0f;
         }
         A0[idx] = v;
-        if (CELL == ELM_CELL_GRU) A1[idx] = (k == xcol + d) ? 1.0f : 0.0f;
+        if (CELL == ELM_CELL_GRU) A1[idx] = (k == d) ? 1.0f : 0.0f;
     }
 
     const int nx = S * d;                          // input values per step for this tile
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             const int e = tid + q * kThreads;
             if (e < nx) {
                 const int s = e / d, dd = e - s * d;
-                buf[s * R + xcol + dd] = xr[q];
+                buf[s * R + dd] = xr[q];
             }
         }
     };
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
         for (int e = tid; e < nx; e += kThreads) {
             const int s = e / d, dd = e - s * d;
             const int64_t row = row0 + s;
-            buf[s * R + xcol + dd] =
+            buf[s * R + dd] =
                 (row < p.N) ? p.X[row * p.ldx_n + (int64_t)t * p.ldx_q + dd] : 0.0f;
         }
     };
@@ -261,6 +262,8 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
         }
         const bool more = (t + 1 < p.Q_run);
         const unsigned wrot = (unsigned)slot * p.copy_bytes;
+        // k-groups that can be non-zero at this step: the input columns and the history slots written so far
+        const int KGt = (p.ring > 1) ? min(KG, (hoff + min(t, p.ring) * L + 7) >> 3) : KG;
         if (x_prefetch && more) load_x(t + 1);
 
         if (CELL != ELM_CELL_GRU) {
@@ -283,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         // the weight queue of each contraction is filled one phase early (before the
                         // point-wise work of the previous contraction), so the first MFMA never waits
                         const int jn = ((ch + 1 < NCH) && ((ch + 1) * 4 + wave < p.nJB)) ? jb + 4 : wave;
-                        contract_main<2, 4, 0, 3, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KG, lane);   // gates i, g
+                        contract_main<2, 4, 0, 3, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KGt, lane);   // gates i, g
                         prefetch_weights<2, 4, 1, 1, 6>(bq2, wrs, wbase, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                                 acc[0][ms][i] = 0.0f;
                                 acc[1][ms][i] = 0.0f;
                             }
-                        contract_main<2, 4, 1, 1, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KG, lane);   // gates f, o
+                        contract_main<2, 4, 1, 1, MS, 6>(acc, bq2, A0 + rbase * R, R, wrs, wbase, KGt, lane);   // gates f, o
                         prefetch_weights<2, 4, 0, 3, 6>(bq2, wrs, (unsigned)(jn * KG * G) * 1024u, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
@@ -313,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                             for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
                                 for (int i = 0; i < 16; ++i) acc[g][ms][i] = 0.0f;
-                        contract<G, G, 0, 1, MS, PF>(acc, A0 + rbase * R, R, wrs, wbase, KG, lane);
+                        contract<G, G, 0, 1, MS, PF>(acc, A0 + rbase * R, R, wrs, wbase, KGt, lane);
 #pragma unroll
                         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
             {
                 // lane base address, made opaque per step so that the 32*NCH store addresses are
                 // recomputed here (scalar row offsets) instead of being kept live across the unroll
-                int lane_base = (rbase + 4 * (lane >> 5)) * R + col_in;
+                int lane_base = (rbase + 4 * (lane >> 5)) * R + hoff + col_in;
                 asm volatile("" : "+v"(lane_base));
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                         for (int i = 0; i < 16; ++i) {
                             hn[ch][ms][i] = sigmoid_f(acc[0][ms][i]);
                             const float r = sigmoid_f(acc[1][ms][i]);
-                            if (col < L) A1[acc_row(ms, i) * R + col] = r * st[ch][ms][i];
+                            if (col < L) A1[acc_row(ms, i) * R + hoff + col] = r * st[ch][ms][i];
                         }
                 }
             }
@@ -405,7 +408,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
                             const float z = hn[ch][ms][i];
                             const float hv = (1.0f - z) * st[ch][ms][i] + z * tanh_f(acc[0][ms][i]);
                             st[ch][ms][i] = hv;
-                            if (col < L) A0[acc_row(ms, i) * R + col] = hv;
+                            if (col < L) A0[acc_row(ms, i) * R + hoff + col] = hv;
                         }
                 }
             }
@@ -420,7 +423,7 @@ __global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
     for (int idx = tid; idx < S * L; idx += kThreads) {
         const int s = idx / L, j = idx - s * L;
         const int64_t row = row0 + s;
-        if (row < p.N) p.H[row * L + j] = A0[s * R + slot * L + j];
+        if (row < p.N) p.H[row * L + j] = A0[s * R + hoff + slot * L + j];
     }
     if (CELL == ELM_CELL_LSTM && p.C != nullptr) {
 #pragma unroll
@@ -516,7 +519,7 @@ PackedLayout packed_layout(int cell, int d, int L, int ring) {
     return lay;
 }
 
-// Fully connected multi-lag cell: `ring` rotations of the packed operand [A_k(0); A_k(1); ...; W; b].
+// Fully connected multi-lag cell: `ring` rotations of the packed operand [W; b; A_k(0); A_k(1); ...].
 // Rotation c is used at the steps t with t % ring == c, when history slot s holds the state of
 // 1 + (c - 1 - s) mod ring steps ago; A is [Q][L][L] (lag k in block k-1).
 void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, const float* b, float* out) {
@@ -531,15 +534,15 @@ void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, co
                         const int k = kg * 8 + (lane >> 5) * 4 + e;
                         const int j = jb * 32 + (lane & 31);
                         if (k >= lay.K || j >= L) continue;
-                        float v;
-                        if (k < ring * L) {
-                            const int s = k / L, m = k - s * L;
+                        float v;                      // operand rows: input, bias, history slots
+                        if (k < d) {
+                            v = W[(size_t)k * L + j];
+                        } else if (k == d) {
+                            v = b[j];
+                        } else {
+                            const int s = (k - d - 1) / L, m = (k - d - 1) - s * L;
                             const int lag = 1 + (((c - 1 - s) % ring) + ring) % ring;
                             v = A[((size_t)(lag - 1) * L + m) * L + j];
-                        } else if (k < ring * L + d) {
-                            v = W[(size_t)(k - ring * L) * L + j];
-                        } else {
-                            v = b[j];
                         }
                         oc[(((size_t)jb * lay.KG + kg) * 64 + lane) * 4 + e] = v;
                     }
@@ -558,10 +561,10 @@ void pack_weights(const PackedLayout& lay, const float* W, const float* U, const
                         const int j = jb * 32 + (lane & 31);
                         if (k >= lay.K || j >= L) continue;
                         const int col = g * L + j;
-                        float v;
-                        if (k < L) v = U[(size_t)k * GL + col];
-                        else if (k < L + d) v = W[(size_t)(k - L) * GL + col];
-                        else v = b[col];
+                        float v;                      // operand rows: input, bias, recurrent
+                        if (k < d) v = W[(size_t)k * GL + col];
+                        else if (k == d) v = b[col];
+                        else v = U[(size_t)(k - d - 1) * GL + col];
                         out[((((size_t)jb * lay.KG + kg) * G + g) * 64 + lane) * 4 + e] = v;
                     }
 }

@@ -29,7 +29,7 @@ from scipy.signal import lfilter
 @dataclass(frozen=True)
 class ElmConfig:
     name: str
-    cell: str            # "elman" | "lstm" | "gru" | "elman_diag"
+    cell: str            # "elman" | "lstm" | "gru" | "elman_diag" | "fc_multilag"
     N: int               # number of windows (training samples)
     Q: int               # steps per window
     d: int               # input channels
@@ -57,6 +57,8 @@ CONFIGS = (
 # Q = 50, M = 100, univariate).
 EXTRA_CONFIGS = (
     ElmConfig("paper_elman", "elman_diag", 1_000_000, 50, 1, 100, 1, 0.3, 0.0, 0.0, False, 0.05, 13257),
+    # the paper's fully connected multi-lag cell at Q = 10 (the window of most of its datasets), M = 100
+    ElmConfig("paper_fc", "fc_multilag", 1_000_000, 10, 4, 100, 1, 0.1, 0.0, 0.0, False, 0.05, 13258),
 )
 
 
