@@ -480,8 +480,10 @@ hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t l
     // narrow layers: one or two column blocks only, so the waves split the rows of a larger tile
     int wr = (a.nJB == 1) ? 4 : (a.nJB == 2) ? 2 : 1;
     if (lds_per_row * 32 * ms * wr > lds_max) wr = 1;
-    // fewer tiles than compute units: halve the tile so that twice as many work-groups run
-    if (ms == 2 && (N + 64 * wr - 1) / (64 * wr) < 256) ms = 1;
+    // fewer tiles than compute units: halve the tile so that twice as many work-groups run; layers of
+    // one column chunk (L <= 128) also run 32-row blocks per wave: their variants need under 256
+    // registers, so two or more waves share a SIMD and one wave's gate math overlaps another's matrix work
+    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < 256 || nch == 1)) ms = 1;
     if (wr > 1) {
         const int Sw = 32 * ms * wr;
         const int64_t tiles = (N + Sw - 1) / Sw;
