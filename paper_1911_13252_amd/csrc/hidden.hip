@@ -143,8 +143,11 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
 // spare LDS instead of registers; used by the largest LSTM variants, which otherwise spill.
 // WR > 1 (narrow layers, L <= 64, one column chunk): the four waves share 4/WR column blocks and split
 // the tile's rows into WR groups of 32*MS instead, so that no wave is idle.
+// Variants that fit 256 registers (32-row blocks, one column chunk, or two for the cells with at most
+// three gates) are compiled for two waves per SIMD: one wave's gate math overlaps another's matrix work.
 template <int CELL, int MS, int NCH, int STAGE, int WR>
-__global__ __launch_bounds__(kThreads) void hidden_kernel(const HiddenArgs p) {
+__global__ __launch_bounds__(kThreads, (MS == 1 && (NCH == 1 || (NCH == 2 && CELL != ELM_CELL_LSTM))) ? 2 : 1)
+void hidden_kernel(const HiddenArgs p) {
     static_assert(WR == 1 || NCH == 1, "rows are split over the waves only when one column chunk exists");
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS * WR;
@@ -481,9 +484,10 @@ hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t l
     int wr = (a.nJB == 1) ? 4 : (a.nJB == 2) ? 2 : 1;
     if (lds_per_row * 32 * ms * wr > lds_max) wr = 1;
     // fewer tiles than compute units: halve the tile so that twice as many work-groups run; layers of
-    // one column chunk (L <= 128) also run 32-row blocks per wave: their variants need under 256
-    // registers, so two or more waves share a SIMD and one wave's gate math overlaps another's matrix work
-    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < 256 || nch == 1)) ms = 1;
+    // one column chunk (L <= 128; two chunks for Elman and GRU) also run 32-row blocks per wave: those
+    // variants fit 256 registers, so two or more waves share a SIMD
+    const bool two_waves = nch == 1 || (nch == 2 && CELL != ELM_CELL_LSTM);
+    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < 256 || two_waves)) ms = 1;
     if (wr > 1) {
         const int Sw = 32 * ms * wr;
         const int64_t tiles = (N + Sw - 1) / Sw;

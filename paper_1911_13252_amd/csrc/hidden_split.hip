@@ -261,8 +261,11 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const char* __r
 // once, when the operand is rebuilt.
 // WR > 1 (narrow layers, L <= 64, one column chunk): the four waves share 4/WR column blocks and split
 // the tile's rows into WR groups of 32*MS instead, so that no wave is idle.
+// Variants that fit 256 registers (32-row blocks, one column chunk) are compiled for two waves per
+// SIMD: one wave's gate math overlaps another's matrix work.
 template <int CELL, int MS, int NCH, int STAGE, int WR>
-__global__ __launch_bounds__(kThreads) void hidden_split_kernel(const SplitArgs p) {
+__global__ __launch_bounds__(kThreads, (MS == 1 && NCH == 1) ? 2 : 1)
+void hidden_split_kernel(const SplitArgs p) {
     static_assert(WR == 1 || NCH == 1, "rows are split over the waves only when one column chunk exists");
     constexpr int G = (CELL == ELM_CELL_ELMAN) ? 1 : (CELL == ELM_CELL_LSTM) ? 4 : 3;
     constexpr int S = 32 * MS * WR;
@@ -609,8 +612,10 @@ hipError_t launch_cell(int ms, int nch, const SplitArgs& a, int64_t N, size_t ld
     // narrow layers: one or two column blocks only, so the waves split the rows of a larger tile
     int wr = (a.nJB == 1) ? 4 : (a.nJB == 2) ? 2 : 1;
     if (lds_per_row * 32 * ms * wr > lds_max) wr = 1;
-    // fewer tiles than compute units: halve the tile so that twice as many work-groups run
-    if (ms == 2 && (N + 64 * wr - 1) / (64 * wr) < 256) ms = 1;
+    // fewer tiles than compute units: halve the tile so that twice as many work-groups run; layers of
+    // one column chunk (L <= 128) also run 32-row blocks per wave: those variants fit 256 registers,
+    // so two waves share a SIMD
+    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < 256 || nch == 1)) ms = 1;
     if (wr > 1) {
         const int Sw = 32 * ms * wr;
         const int64_t tiles = (N + Sw - 1) / Sw;
