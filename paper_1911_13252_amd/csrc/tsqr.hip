@@ -99,29 +99,64 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
     __syncthreads();
 
     for (int blk = blk_begin; blk < blk_end; ++blk) {
-        // ---- load the block into LDS (zero padded)
+        // ---- load the block into LDS (zero padded).  A wave takes 8 rows at a time and issues all of
+        // their loads before the first LDS store, so a block costs a handful of memory round trips.
         int p0 = 0;
-        if (!a.combine) {
-            const int64_t r0 = (int64_t)blk * BR;
-            for (int idx = tid; idx < BR * np; idx += kThreads) {
-                const int r = idx / np, c = idx - r * np;
-                const int64_t row = r0 + r;
-                float v = 0.0f;
-                if (row < a.nrows) {
-                    if (c < a.nc0) v = a.src0[row * a.ld0 + c];
-                    else if (c < a.nc0 + a.nc1) v = a.src1[row * a.ld1 + (c - a.nc0)];
-                }
-                Bs[r * ldb + c] = v;
+        {
+            const float* src0;
+            const float* src1 = a.src1;
+            int64_t ld0, row_first, row_limit;
+            int nc0, nc1;
+            if (!a.combine) {
+                src0 = a.src0; ld0 = a.ld0; nc0 = a.nc0; nc1 = a.nc1;
+                row_first = (int64_t)blk * BR; row_limit = a.nrows;
+            } else {
+                const int ri = blk / per_r, slice = blk - ri * per_r;
+                src0 = a.src0 + (size_t)ri * np * np; ld0 = np; nc0 = np; nc1 = 0;
+                row_first = (int64_t)slice * BR; row_limit = np;
+                p0 = (slice * BR) / kNB;                        // columns left of the slice are zero
             }
-        } else {
-            const int ri = blk / per_r, slice = blk - ri * per_r;
-            const float* src = a.src0 + (size_t)ri * np * np;
-            const int rbase = slice * BR;
-            p0 = rbase / kNB;                                   // columns left of the slice are zero
-            for (int idx = tid; idx < BR * np; idx += kThreads) {
-                const int r = idx / np, c = idx - r * np;
-                const int row = rbase + r;
-                Bs[r * ldb + c] = (row < np) ? src[(size_t)row * np + c] : 0.0f;
+            constexpr int U = 8;
+            const bool vec4 = ((nc0 & 3) == 0) && ((ld0 & 3) == 0) &&
+                              ((reinterpret_cast<uintptr_t>(src0) & 15) == 0);
+            for (int rb = wave * U; rb < BR; rb += 4 * U) {
+                if (vec4) {
+                    for (int c = lane * 4; c < nc0; c += 256) {
+                        float4 v[U];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const int64_t row = row_first + rb + u;
+                            v[u] = (row < row_limit) ? *reinterpret_cast<const float4*>(src0 + row * ld0 + c)
+                                                     : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            float* dst = Bs + (rb + u) * ldb + c;
+                            dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
+                        }
+                    }
+                } else {
+                    for (int c = lane; c < nc0; c += 64) {
+                        float v[U];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const int64_t row = row_first + rb + u;
+                            v[u] = (row < row_limit) ? src0[row * ld0 + c] : 0.0f;
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) Bs[(rb + u) * ldb + c] = v[u];
+                    }
+                }
+                for (int c = nc0 + lane; c < np; c += 64) {       // targets, then zero padding
+                    float v[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t row = row_first + rb + u;
+                        v[u] = (row < row_limit && c < nc0 + nc1) ? src1[row * a.ld1 + (c - nc0)] : 0.0f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) Bs[(rb + u) * ldb + c] = v[u];
+                }
             }
         }
         __syncthreads();
