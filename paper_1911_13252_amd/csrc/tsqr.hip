@@ -240,19 +240,35 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
 #pragma unroll
                 for (int l = 0; l < 32; ++l) {
                     tv[l] = taus[l];
-                    t[l] = 0.0f;
+                    t[l] = (l == j) ? tv[l] : 0.0f;
                 }
+                // Row i of the Gram matrix is read in 16-byte pieces starting at the multiple of four at
+                // or below i + 1 (the entries at or left of the diagonal in the first piece are skipped);
+                // row i - 1 is requested before row i is used, so the LDS latency hides behind the FMAs.
+                float4 gq[2][8];
 #pragma unroll
-                for (int l = 0; l < 32; ++l) t[l] = (l == j) ? tv[l] : 0.0f;
+                for (int c = 7; c < 8; ++c) gq[0][c] = *reinterpret_cast<const float4*>(Gs + 30 * kGs + 4 * c);
 #pragma unroll
                 for (int i = 30; i >= 0; --i) {
-                    float s0 = 0.0f, s1 = 0.0f;
+                    const int cur = (30 - i) & 1;
+                    if (i > 0) {
 #pragma unroll
-                    for (int l = i + 1; l < 32; ++l) {
-                        const float gv = Gs[i * kGs + l];       // same address in every lane
-                        if ((l - i) & 1) s0 = fmaf(gv, t[l], s0); else s1 = fmaf(gv, t[l], s1);
+                        for (int c = (i >> 2); c < 8; ++c)        // chunks of row i - 1: from i / 4
+                            gq[cur ^ 1][c] = *reinterpret_cast<const float4*>(Gs + (i - 1) * kGs + 4 * c);
                     }
-                    t[i] = (i < j) ? -tv[i] * (s0 + s1) : t[i];
+                    __builtin_amdgcn_sched_barrier(0);
+                    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;      // four short dependency chains
+#pragma unroll
+                    for (int c = ((i + 1) >> 2); c < 8; ++c) {
+                        const float4 gv = gq[cur][c];
+                        const int l4 = 4 * c;
+                        if (l4 + 0 > i) s0 = fmaf(gv.x, t[l4 + 0], s0);
+                        if (l4 + 1 > i) s1 = fmaf(gv.y, t[l4 + 1], s1);
+                        if (l4 + 2 > i) s2 = fmaf(gv.z, t[l4 + 2], s2);
+                        if (l4 + 3 > i) s3 = fmaf(gv.w, t[l4 + 3], s3);
+                    }
+                    t[i] = (i < j) ? -tv[i] * ((s0 + s1) + (s2 + s3)) : t[i];
+                    __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
                 for (int i = 0; i < 32; ++i) Ts[i * kTs + j] = t[i];
