@@ -275,13 +275,13 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const float* __restric
 // owns a row at a time (lane l holds columns l, l+64, ...), beta and the gradient accumulators
 // live in registers, the row dot products are reduced with wavefront shuffles, and there is no
 // work-group barrier inside the row loop.
-template <int M, int MODE>
+template <int M, int MODE, int EPL>
 __global__ __launch_bounds__(kThreads) void stream_rows_kernel(const float* __restrict__ H,
                                                                const float* __restrict__ T, int64_t N, int L,
                                                                int m, const double* __restrict__ beta,
                                                                double* __restrict__ part,
                                                                float* __restrict__ Y) {
-    constexpr int EPL = 8;                        // columns per lane: L <= 512
+    // EPL = columns per lane (L <= 64 * EPL)
     __shared__ double wsum[EPL * 64 * M + 2];     // in-group sum of the 4 waves' results
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     double bt[EPL][M], gacc[EPL][M];
@@ -441,21 +441,21 @@ hipError_t launch_stream(const float* H, const float* T, int64_t N, int L, int m
     const int grid = stream_grid(N);
     int M = 1;
     while (M < m) M *= 2;
-    if (M <= 4 && L <= 512) {       // register-resident variant
+    if (M <= 4 && L <= 512) {       // register-resident variant, columns per lane sized to L
+#define ELM_ROWS_LAUNCH(MM, EE)                                                                        \
+    hipLaunchKernelGGL((stream_rows_kernel<MM, MODE, EE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N, L, \
+                       m, beta, part, Y)
+#define ELM_ROWS_CASE(MM)                                   \
+    if (L <= 128) ELM_ROWS_LAUNCH(MM, 2);                   \
+    else if (L <= 256) ELM_ROWS_LAUNCH(MM, 4);              \
+    else ELM_ROWS_LAUNCH(MM, 8)
         switch (M) {
-            case 1:
-                hipLaunchKernelGGL((stream_rows_kernel<1, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
-                                   L, m, beta, part, Y);
-                break;
-            case 2:
-                hipLaunchKernelGGL((stream_rows_kernel<2, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
-                                   L, m, beta, part, Y);
-                break;
-            default:
-                hipLaunchKernelGGL((stream_rows_kernel<4, MODE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N,
-                                   L, m, beta, part, Y);
-                break;
+            case 1: ELM_ROWS_CASE(1); break;
+            case 2: ELM_ROWS_CASE(2); break;
+            default: ELM_ROWS_CASE(4); break;
         }
+#undef ELM_ROWS_CASE
+#undef ELM_ROWS_LAUNCH
         return hipGetLastError();
     }
     const size_t lds = stream_lds_bytes(L, M);
