@@ -14,7 +14,7 @@ struct elm_rnn_model {
     int cell, Q, d, L, m, G;
     elm::PackedLayout lay;
     std::vector<float> W, U, b;   // host copies, float32
-    float* dWp = nullptr;         // packed [U; W; b] on the device (dense cells)
+    float* dWp = nullptr;         // packed [W; b; U] on the device (dense cells; rotations for the multi-lag cell)
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights

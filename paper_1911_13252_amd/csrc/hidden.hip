@@ -10,7 +10,8 @@
 //
 // Differences from the paper's Opt-PR-ELM kernel (Algorithm "Opt-PR-ELM", one thread per
 // (sample, neuron) with BSxBS shared-memory tiles): the per-step H(t) is never stored, the
-// recurrence is a dense L x L lag-1 matrix, and the tiling is by 64-lane wavefront MFMA tiles.
+// recurrence is a dense L x L lag-1 matrix (or, for the paper's fully connected cell, one dense matrix
+// per lag over a ring of past states), and the tiling is by 64-lane wavefront MFMA tiles.
 
 #include "internal.h"
 

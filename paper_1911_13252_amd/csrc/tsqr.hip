@@ -2,11 +2,11 @@
 // "Computing beta": H = QR, z = Q^T Y; applying the reflectors to [H | T] yields R and z at once).
 //
 // Every work-group keeps its own upper-triangular R (np x np, global memory, L2 resident) and
-// folds 64-row blocks of the input into it, one after the other:  [R; B] -> [R'; 0].  Because R is
-// triangular, the reflector that eliminates column k only touches row k of R and the whole block,
-// so V = [I; V_B] and one fold costs 2*64*n^2 flops: no work is spent on the zero triangle.
+// folds BR-row blocks (64 or 128 rows) of the input into it, one after the other:
+// [R; B] -> [R'; 0].  Because R is triangular, the reflector that eliminates column k only touches row k of R and the whole block,
+// so V = [I; V_B] and one fold costs 2*BR*n^2 flops: no work is spent on the zero triangle.
 // Per panel of 32 columns:
-//   * panel factorisation on the VALU: lanes hold 8 rows of one panel column in registers, the
+//   * panel factorisation on the VALU: lanes hold BR/8 rows of one panel column in registers, the
 //     Householder norm and all dot products of a step come from ONE reduction (wavefront shuffle
 //     inside a wave, a 4-entry LDS exchange across the 4 waves);
 //   * the triangular factor T of the compact-WY form Q = I - V T V^T from the Gram matrix of V_B;
@@ -35,7 +35,7 @@ struct FoldArgs {
     int64_t ld0, ld1;
     int nc0, nc1;
     int64_t nrows;       // level 0: N
-    int nblocks;         // level 0: number of 64-row blocks
+    int nblocks;         // level 0: number of BR-row blocks
     int nprev;           // combine: number of R factors in the previous stack
     int combine;         // 0 / 1
     float* Rout;         // [gridDim.x][np][np]
