@@ -180,6 +180,32 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
                 float* H_out, float* beta_out, double* beta64_out,
                 elm_rnn_stats* stats, elm_rnn_model** model_out);
 
+/* ---- the whole fit without an N x L hidden matrix in memory ----------------------------------- */
+
+/* Workspace for elm_rnn_fit_streamed: the solve workspace plus one chunk of H (chunk_rows x L floats;
+ * chunk_rows <= 0 selects the default, about 128 MiB of H; other values are rounded up to a multiple of
+ * 128 rows and capped at N). */
+size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows);
+
+/* Algorithm "S-R-ELM" with steps (2) and (3) interleaved: only H(Q) enters step (3), and the R factor
+ * of [H | T] can absorb H a block of rows at a time, so H is produced one chunk of rows at a time and
+ * folded into the per-work-group R factors of the TSQR before the next chunk overwrites it.  The
+ * N x L matrix never exists; the chunk buffer is small enough to stay in the memory-side cache.
+ * Same arguments and results as elm_rnn_fit (there is no H_out), and the same beta up to float32
+ * rounding in the factorisation, except:
+ *   refine = 0      beta is the plain float32 TSQR solution; stats->rmse is read off the R factor
+ *                   (= rmse_qr) and stats->ne_resid is NaN (no pass over H with the final beta exists);
+ *   refine = 1..4   that many float64-residual refinement steps, each of which recomputes H chunk by
+ *                   chunk (one more run of step (2)), plus one more run for the statistics;
+ *   refine = -1     refine twice if max|R_jj| > 30 min|R_jj| (the unrefined normal-equation residual is
+ *                   about 1e-8 .. 6e-8 times that ratio), else not at all.
+ * stats->t_hidden_ms sums every run of step (2); stats->refine_iters reports the steps taken. */
+int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T,
+                         int64_t N, int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
+                         int64_t chunk_rows, int refine, void* workspace, size_t workspace_bytes,
+                         void* hip_stream, float* beta_out, double* beta64_out,
+                         elm_rnn_stats* stats, elm_rnn_model** model_out);
+
 /* Workspace for elm_rnn_predict: N*L floats for H. */
 size_t elm_rnn_predict_workspace_bytes(int64_t N, int L);
 

@@ -8,14 +8,15 @@ use and a missing library is a hard error (there is no CPU fallback).
 """
 from .binding import (CELLS, ElmRnnError, FitResult, Model, Stats, fit, hidden, lib_path,
                       load_library, predict, solve, solve_workspace_bytes,
-                      fit_workspace_bytes, DECLARED_SYMBOLS)
+                      fit_workspace_bytes, fit_streamed, fit_streamed_workspace_bytes, DECLARED_SYMBOLS)
 
 __all__ = ["CELLS", "ElmRnnError", "FitResult", "Model", "Stats", "fit", "hidden", "lib_path",
            "load_library", "predict", "solve", "solve_workspace_bytes", "fit_workspace_bytes",
-           "DECLARED_SYMBOLS"]
+           "fit_streamed", "fit_streamed_workspace_bytes", "DECLARED_SYMBOLS"]
 
 # the C entry points' own names, for callers that think in terms of include/elm_rnn.h
 elm_rnn_fit = fit
+elm_rnn_fit_streamed = fit_streamed
 elm_rnn_hidden = hidden
 elm_rnn_solve = solve
 elm_rnn_predict = predict

@@ -17,6 +17,7 @@ DECLARED_SYMBOLS = (
     "elm_rnn_model_create", "elm_rnn_model_create_from_weights", "elm_rnn_get_weights",
     "elm_rnn_model_set_contraction", "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
     "elm_rnn_solve", "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
+    "elm_rnn_fit_streamed_workspace_bytes", "elm_rnn_fit_streamed",
     "elm_rnn_predict_workspace_bytes", "elm_rnn_predict", "elm_rnn_strerror",
     "elm_rnn_last_hip_error",
 )
@@ -89,6 +90,11 @@ def load_library():
     lib.elm_rnn_fit_workspace_bytes.restype = sz
     lib.elm_rnn_fit.argtypes = [C.c_int, vp, i64, i64, vp, i64, C.c_int, C.c_int, C.c_int, C.c_int, u64,
                                 C.POINTER(_Init), vp, sz, vp, vp, vp, vp, C.POINTER(_Stats), C.POINTER(vp)]
+    lib.elm_rnn_fit_streamed_workspace_bytes.argtypes = [i64, C.c_int, C.c_int, i64]
+    lib.elm_rnn_fit_streamed_workspace_bytes.restype = sz
+    lib.elm_rnn_fit_streamed.argtypes = [C.c_int, vp, i64, i64, vp, i64, C.c_int, C.c_int, C.c_int, C.c_int, u64,
+                                         C.POINTER(_Init), i64, C.c_int, vp, sz, vp, vp, vp, C.POINTER(_Stats),
+                                         C.POINTER(vp)]
     lib.elm_rnn_predict_workspace_bytes.argtypes = [i64, C.c_int]
     lib.elm_rnn_predict_workspace_bytes.restype = sz
     lib.elm_rnn_predict.argtypes = [vp, vp, i64, i64, i64, vp, vp, sz, vp]
@@ -313,6 +319,41 @@ def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0,
                          C.byref(st), C.byref(out))
     _check(rc, allow_rank=allow_rank_deficient)
     return FitResult(Model(out.value, cell, Q, d, L, m), beta32, beta64, H, _stats(st, rc == ELM_ERANK))
+
+
+def fit_streamed_workspace_bytes(N: int, L: int, m: int, chunk_rows: int = 0) -> int:
+    return int(load_library().elm_rnn_fit_streamed_workspace_bytes(N, L, m, chunk_rows))
+
+
+def fit_streamed(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0, forget_bias=0.0,
+                 zero_bias=False, contraction="fp32", chunk_rows: int = 0, refine: int = -1, workspace=None,
+                 stream=None, allow_rank_deficient: bool = False) -> FitResult:
+    """elm_rnn_fit_streamed: the fit with H produced and consumed chunk by chunk (FitResult.H is None)."""
+    import torch
+    lib = load_library()
+    _dev_f32(X, "X")
+    _dev_f32(T, "T")
+    if T.dim() == 1:
+        T = T[:, None]
+    if not T.is_contiguous():
+        raise ValueError("T must be contiguous")
+    N, Q, d = X.shape
+    m = T.shape[1]
+    ldn, ldq = _x_strides(X)
+    need = fit_streamed_workspace_bytes(N, L, m, chunk_rows)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    beta32 = torch.empty((L, m), dtype=torch.float32, device=X.device)
+    beta64 = torch.empty((L, m), dtype=torch.float64, device=X.device)
+    st = _Stats()
+    out = C.c_void_p()
+    init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias, contraction)
+    rc = lib.elm_rnn_fit_streamed(CELLS[cell], X.data_ptr(), ldn, ldq, T.data_ptr(), N, Q, d, L, m,
+                                  C.c_uint64(seed), C.byref(init), chunk_rows, refine, workspace.data_ptr(),
+                                  workspace.numel(), _stream_ptr(stream), beta32.data_ptr(), beta64.data_ptr(),
+                                  C.byref(st), C.byref(out))
+    _check(rc, allow_rank=allow_rank_deficient)
+    return FitResult(Model(out.value, cell, Q, d, L, m), beta32, beta64, None, _stats(st, rc == ELM_ERANK))
 
 
 def predict(model: Model, X, workspace=None, stream=None):

@@ -432,6 +432,150 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
     return rc;
 }
 
+// rows of H per chunk of the streamed fit
+static int64_t streamed_chunk(int64_t N, int L, int64_t chunk_rows) {
+    if (chunk_rows <= 0) {
+        // about 128 MiB of H: the chunk stage 1 writes is still in the memory-side cache when level 0
+        // of the TSQR reads it, and both kernels get a whole number of rounds of work-groups
+        chunk_rows = (((int64_t)128 << 20) / (4 * (int64_t)L)) / 32768 * 32768;
+        if (chunk_rows < 32768) chunk_rows = 32768;
+    }
+    chunk_rows = (chunk_rows + 127) / 128 * 128;       // whole row blocks of the TSQR
+    return chunk_rows < N ? chunk_rows : N;
+}
+
+size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows) {
+    const size_t s = elm_rnn_solve_workspace_bytes(N, L, m);
+    if (s == 0) return 0;
+    return s + (((size_t)streamed_chunk(N, L, chunk_rows) * L * sizeof(float) + 255) & ~(size_t)255);
+}
+
+// max|R_jj| / min|R_jj| above which the automatic mode of the streamed fit refines beta: the normal-equation
+// residual of the unrefined float32 solution grows like 1e-8 .. 6e-8 times this ratio
+static constexpr double kStreamedRefineRatio = 30.0;
+
+int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T, int64_t N,
+                         int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
+                         int64_t chunk_rows, int refine, void* workspace, size_t workspace_bytes,
+                         void* hip_stream, float* beta_out, double* beta64_out, elm_rnn_stats* stats,
+                         elm_rnn_model** model_out) {
+    if (X == nullptr || T == nullptr || beta_out == nullptr || model_out == nullptr) return ELM_EINVAL;
+    if (N < 1 || N < L || refine < -1 || refine > 4 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    int rc = check_dims(cell, Q, d, L, m);
+    if (rc != ELM_OK) return rc;
+    const size_t need = elm_rnn_fit_streamed_workspace_bytes(N, L, m, chunk_rows);
+    if (need == 0) return ELM_EUNSUPPORTED;
+    if (workspace == nullptr || workspace_bytes < need) return ELM_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t chunk = streamed_chunk(N, L, chunk_rows);
+    const SolvePlan plan = make_solve_plan(N, L, m);
+    float* Hc = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.bytes);
+    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(workspace) + plan.off_small);
+
+    elm_rnn_model* mdl = nullptr;
+    rc = elm_rnn_model_create(cell, Q, d, L, m, seed, init, &mdl);
+    if (rc != ELM_OK) return rc;
+
+    // one event pair around every stage-1 launch: their sum is the stage-1 time, the rest of the
+    // span is stage 2
+    struct Events {
+        std::vector<hipEvent_t> ev;
+        ~Events() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
+        hipError_t mark(hipStream_t s) {
+            hipEvent_t e = nullptr;
+            hipError_t rc = hipEventCreate(&e);
+            if (rc != hipSuccess) return rc;
+            ev.push_back(e);
+            return hipEventRecord(e, s);
+        }
+    } span, s1;
+
+    // one sweep over the rows: stage 1 on a chunk, then `consume` on that chunk
+    auto sweep = [&](auto&& consume) -> hipError_t {
+        for (int64_t r0 = 0; r0 < N; r0 += chunk) {
+            const int64_t rows = (N - r0 < chunk) ? N - r0 : chunk;
+            hipError_t e = s1.mark(stream);
+            if (e == hipSuccess)
+                e = run_hidden(mdl, X + r0 * ldx_n, ldx_n, ldx_q, rows, Q, nullptr, nullptr, Hc, nullptr, stream);
+            if (e == hipSuccess) e = s1.mark(stream);
+            if (e == hipSuccess) e = consume(T + r0 * m, rows, r0 > 0);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    };
+    auto fail = [&](hipError_t e, const char* where) {
+        set_hip_error(e, where);
+        elm_rnn_free(mdl);
+        return ELM_EHIP;
+    };
+
+    hipError_t e = span.mark(stream);
+    if (e == hipSuccess)
+        e = sweep([&](const float* Tc, int64_t rows, bool later) {
+            return launch_tsqr_level0(plan, Hc, Tc, rows, workspace, later ? 1 : 0, stream);
+        });
+    float* R = nullptr;
+    if (e == hipSuccess) e = launch_tsqr_combine(plan, workspace, &R, stream);
+    if (e == hipSuccess) e = launch_backsolve(plan, R, workspace, stream);
+    if (e != hipSuccess) return fail(e, "streamed fit: factorisation");
+
+    double sc[8];
+    int updates = refine;
+    if (refine < 0) {
+        e = hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail(e, "streamed fit: condition read-back");
+        updates = (sc[6] == 0.0 && sc[5] > kStreamedRefineRatio * sc[4]) ? 2 : 0;
+    }
+    // every refinement step, and the statistics of the final beta, need H again: it is recomputed
+    for (int it = 0; updates > 0 && it <= updates; ++it) {
+        e = sweep([&](const float* Tc, int64_t rows, bool later) {
+            return launch_residual_chunk(plan, Hc, Tc, rows, workspace, later ? 1 : 0, stream);
+        });
+        if (e == hipSuccess) e = launch_residual_finish(plan, workspace, stream);
+        if (e == hipSuccess && it < updates) e = launch_refine_update(plan, R, workspace, stream);
+        if (e != hipSuccess) return fail(e, "streamed fit: refinement");
+    }
+    e = launch_export_beta(plan, workspace, beta_out, beta64_out, stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(mdl->dBeta, small + SmallArea::BETA, (size_t)L * m * sizeof(double),
+                           hipMemcpyDeviceToDevice, stream);
+    if (e == hipSuccess) e = span.mark(stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(e, "streamed fit: epilogue");
+
+    if (stats != nullptr) {
+        float total = 0.0f;
+        double hidden = 0.0;
+        e = hipEventElapsedTime(&total, span.ev[0], span.ev[1]);
+        for (size_t i = 0; e == hipSuccess && i + 1 < s1.ev.size(); i += 2) {
+            float ms = 0.0f;
+            e = hipEventElapsedTime(&ms, s1.ev[i], s1.ev[i + 1]);
+            hidden += ms;
+        }
+        if (e != hipSuccess) return fail(e, "streamed fit: timing");
+        const double nm = (double)N * m;
+        stats->t_hidden_ms = hidden;
+        stats->t_solve_ms = total - hidden;
+        stats->rmse_qr = std::sqrt(sc[3] / nm);
+        if (updates > 0) {
+            stats->rmse = std::sqrt(sc[0] / nm);
+            const double den = std::sqrt(sc[1]) * std::sqrt(sc[0]);
+            stats->ne_resid = den > 0.0 ? std::sqrt(sc[2]) / den : 0.0;
+        } else {           // no pass over H with the final beta was made
+            stats->rmse = stats->rmse_qr;
+            stats->ne_resid = std::nan("");
+        }
+        stats->r_diag_min = sc[4];
+        stats->r_diag_max = sc[5];
+        stats->refine_iters = updates;
+    }
+    *model_out = mdl;
+    return sc[6] != 0.0 ? ELM_ERANK : ELM_OK;
+}
+
 size_t elm_rnn_predict_workspace_bytes(int64_t N, int L) {
     if (N < 1 || L < 1) return 0;
     return ((size_t)N * L * sizeof(float) + 255) & ~(size_t)255;

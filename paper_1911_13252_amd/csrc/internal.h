@@ -80,9 +80,16 @@ SolvePlan make_solve_plan(int64_t N, int L, int m);
 
 hipError_t launch_tsqr(const SolvePlan& plan, const float* H, const float* T, void* ws,
                        float** R_final, hipStream_t stream);
+// The two halves of launch_tsqr, for callers that hand the rows over in chunks.
+hipError_t launch_tsqr_level0(const SolvePlan& plan, const float* H, const float* T, int64_t rows, void* ws,
+                              int keep, hipStream_t stream);
+hipError_t launch_tsqr_combine(const SolvePlan& plan, void* ws, float** R_final, hipStream_t stream);
 hipError_t launch_backsolve(const SolvePlan& plan, const float* R, void* ws, hipStream_t stream);
 hipError_t launch_residual_pass(const SolvePlan& plan, const float* H, const float* T, void* ws,
                                 hipStream_t stream);
+hipError_t launch_residual_chunk(const SolvePlan& plan, const float* H, const float* T, int64_t rows, void* ws,
+                                 int accumulate, hipStream_t stream);
+hipError_t launch_residual_finish(const SolvePlan& plan, void* ws, hipStream_t stream);
 hipError_t launch_refine_update(const SolvePlan& plan, const float* R, void* ws, hipStream_t stream);
 hipError_t launch_export_beta(const SolvePlan& plan, void* ws, float* beta32, double* beta64,
                               hipStream_t stream);

@@ -383,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void stream_rows_kernel(const float* __re
 // partials w = q, q+8, ... of output o; the 8 sub-sums are then added in order.
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part,
                                                                    int nparts, int L, int m,
-                                                                   double* small) {
+                                                                   double* small, int accumulate) {
     __shared__ double sub[8][32];
     const int tid = threadIdx.x, ol = tid & 31, q = tid >> 5;
     const int nout = L * m + 2;
@@ -397,8 +397,9 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
         double t = 0.0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) t += sub[r][ol];
-        if (o < L * m) small[SmallArea::grad(L, m) + o] = t;
-        else small[SmallArea::scal(L, m) + (o - L * m)] = t;       // [0] rss, [1] sum H^2
+        // [0] rss, [1] sum H^2 behind the gradient; a later chunk of rows adds to the earlier ones
+        double* dst = (o < L * m) ? small + SmallArea::grad(L, m) + o : small + SmallArea::scal(L, m) + (o - L * m);
+        *dst = accumulate ? *dst + t : t;
     }
 }
 
@@ -484,20 +485,33 @@ hipError_t launch_backsolve(const SolvePlan& pl, const float* R, void* ws, hipSt
     return hipGetLastError();
 }
 
-hipError_t launch_residual_pass(const SolvePlan& pl, const float* H, const float* T, void* ws,
-                                hipStream_t stream) {
+// Residual statistics of `rows` rows (a chunk of the N rows, or all of them): r = T - H beta, H^T r,
+// sum r^2, sum H^2 in float64; accumulate != 0 adds to what earlier chunks left in the workspace.
+hipError_t launch_residual_chunk(const SolvePlan& pl, const float* H, const float* T, int64_t rows, void* ws,
+                                 int accumulate, hipStream_t stream) {
     char* base = static_cast<char*>(ws);
     double* small = reinterpret_cast<double*>(base + pl.off_small);
     double* part = reinterpret_cast<double*>(base + pl.off_part);
-    hipError_t e = launch_stream<0>(H, T, pl.N, pl.L, pl.m, small + SmallArea::BETA, part, nullptr, stream);
+    hipError_t e = launch_stream<0>(H, T, rows, pl.L, pl.m, small + SmallArea::BETA, part, nullptr, stream);
     if (e != hipSuccess) return e;
     const int nout = pl.L * pl.m + 2;
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((nout + 31) / 32), dim3(kThreads), 0, stream, part,
-                       stream_grid(pl.N), pl.L, pl.m, small);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+                       stream_grid(rows), pl.L, pl.m, small, accumulate);
+    return hipGetLastError();
+}
+
+// After the last chunk: the gradient norm.
+hipError_t launch_residual_finish(const SolvePlan& pl, void* ws, hipStream_t stream) {
+    double* small = reinterpret_cast<double*>(static_cast<char*>(ws) + pl.off_small);
     hipLaunchKernelGGL(grad_norm_kernel, dim3(1), dim3(kThreads), 0, stream, pl.L, pl.m, small);
     return hipGetLastError();
+}
+
+hipError_t launch_residual_pass(const SolvePlan& pl, const float* H, const float* T, void* ws,
+                                hipStream_t stream) {
+    hipError_t e = launch_residual_chunk(pl, H, T, pl.N, ws, 0, stream);
+    if (e != hipSuccess) return e;
+    return launch_residual_finish(pl, ws, stream);
 }
 
 hipError_t launch_refine_update(const SolvePlan& pl, const float* R, void* ws, hipStream_t stream) {

@@ -38,6 +38,7 @@ struct FoldArgs {
     int nblocks;         // level 0: number of BR-row blocks
     int nprev;           // combine: number of R factors in the previous stack
     int combine;         // 0 / 1
+    int keep;            // level 0: fold into the R factors already in Rout (a later chunk of rows)
     float* Rout;         // [gridDim.x][np][np]
     int np, ldb;
 };
@@ -84,7 +85,8 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
     // ---- which blocks does this work-group fold, and what does its R start from?
     int blk_begin, blk_end, per_r = 1;
     if (!a.combine) {
-        for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
+        if (!a.keep)
+            for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
         blk_begin = (int)(((int64_t)a.nblocks * blockIdx.x) / gridDim.x);
         blk_end = (int)(((int64_t)a.nblocks * (blockIdx.x + 1)) / gridDim.x);
     } else {
@@ -376,8 +378,15 @@ SolvePlan make_solve_plan(int64_t N, int L, int m) {
     return pl;
 }
 
-hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void* ws, float** R_final,
-                       hipStream_t stream) {
+namespace {
+
+struct FoldLaunch {
+    void (*kern)(const FoldArgs);
+    int br;
+    size_t lds;
+};
+
+hipError_t fold_launch_config(const SolvePlan& pl, FoldLaunch* fl) {
     int dev = 0, lds_max = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -385,38 +394,65 @@ hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void
     if (e != hipSuccess) return e;
     // 128-row blocks whenever they fit in LDS and the input is tall enough to keep the grid busy
     const bool tall = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max && pl.block_rows == 128;
-    const int br = tall ? 128 : 64;
-    const size_t lds = fold_lds_bytes(pl.np, br);
-    auto kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    fl->br = tall ? 128 : 64;
+    fl->lds = fold_lds_bytes(pl.np, fl->br);
+    fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
+}
+
+}  // namespace
+
+// Level 0 over `rows` rows of H and T: every work-group folds its share of the row blocks into its
+// own R factor, which starts from zero (keep == 0) or from what earlier calls left there (keep != 0:
+// the rows arrive in chunks; the work-group count of the plan is used for every chunk).
+hipError_t launch_tsqr_level0(const SolvePlan& pl, const float* H, const float* T, int64_t rows, void* ws,
+                              int keep, hipStream_t stream) {
+    FoldLaunch fl{};
+    hipError_t e = fold_launch_config(pl, &fl);
     if (e != hipSuccess) return e;
-    char* base = static_cast<char*>(ws);
     FoldArgs a{};
     a.np = pl.np;
     a.ldb = pl.np + 1;
-    for (int lvl = 0; lvl < pl.levels; ++lvl) {
-        float* out = reinterpret_cast<float*>(base + pl.off_R[lvl & 1]);
-        if (lvl == 0) {
-            a.src0 = H; a.ld0 = pl.L; a.nc0 = pl.L;
-            a.src1 = T; a.ld1 = pl.m; a.nc1 = pl.m;
-            a.nrows = pl.N;
-            a.nblocks = (int)((pl.N + br - 1) / br);
-            a.combine = 0; a.nprev = 0;
-        } else {
-            a.src0 = reinterpret_cast<const float*>(base + pl.off_R[(lvl - 1) & 1]);
-            a.ld0 = pl.np; a.nc0 = pl.np;
-            a.src1 = nullptr; a.ld1 = 0; a.nc1 = 0;
-            a.nrows = 0; a.nblocks = 0;
-            a.combine = 1; a.nprev = pl.groups[lvl - 1];
-        }
-        a.Rout = out;
-        hipLaunchKernelGGL(kern, dim3(pl.groups[lvl]), dim3(kThreads), lds, stream, a);
+    a.src0 = H; a.ld0 = pl.L; a.nc0 = pl.L;
+    a.src1 = T; a.ld1 = pl.m; a.nc1 = pl.m;
+    a.nrows = rows;
+    a.nblocks = (int)((rows + fl.br - 1) / fl.br);
+    a.combine = 0; a.nprev = 0; a.keep = keep;
+    a.Rout = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_R[0]);
+    hipLaunchKernelGGL(fl.kern, dim3(pl.groups[0]), dim3(kThreads), fl.lds, stream, a);
+    return hipGetLastError();
+}
+
+// The combine levels: merge the level-0 R factors pairwise until one is left.
+hipError_t launch_tsqr_combine(const SolvePlan& pl, void* ws, float** R_final, hipStream_t stream) {
+    FoldLaunch fl{};
+    hipError_t e = fold_launch_config(pl, &fl);
+    if (e != hipSuccess) return e;
+    char* base = static_cast<char*>(ws);
+    *R_final = reinterpret_cast<float*>(base + pl.off_R[0]);
+    FoldArgs a{};
+    a.np = pl.np;
+    a.ldb = pl.np + 1;
+    a.ld0 = pl.np; a.nc0 = pl.np;
+    a.combine = 1;
+    for (int lvl = 1; lvl < pl.levels; ++lvl) {
+        a.src0 = reinterpret_cast<const float*>(base + pl.off_R[(lvl - 1) & 1]);
+        a.nprev = pl.groups[lvl - 1];
+        a.Rout = reinterpret_cast<float*>(base + pl.off_R[lvl & 1]);
+        hipLaunchKernelGGL(fl.kern, dim3(pl.groups[lvl]), dim3(kThreads), fl.lds, stream, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        *R_final = out;
+        *R_final = a.Rout;
     }
     return hipSuccess;
+}
+
+hipError_t launch_tsqr(const SolvePlan& pl, const float* H, const float* T, void* ws, float** R_final,
+                       hipStream_t stream) {
+    hipError_t e = launch_tsqr_level0(pl, H, T, pl.N, ws, 0, stream);
+    if (e != hipSuccess) return e;
+    return launch_tsqr_combine(pl, ws, R_final, stream);
 }
 
 }  // namespace elm

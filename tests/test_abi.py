@@ -42,6 +42,11 @@ def test_host_only_entry_points(lib):
     assert elm.solve_workspace_bytes(1000, 513, 1) == 0
     assert elm.solve_workspace_bytes(0, 10, 1) == 0
     assert elm.fit_workspace_bytes(1000, 16, 1, True) >= elm.fit_workspace_bytes(1000, 16, 1, False) + 1000 * 16 * 4
+    # the streamed fit holds one chunk of H: whole 128-row blocks, at most N rows, 128 MiB by default
+    assert elm.fit_streamed_workspace_bytes(4_000_000, 512, 2, 1000) - a == 1024 * 512 * 4
+    assert elm.fit_streamed_workspace_bytes(4_000_000, 512, 2) - a == 65536 * 512 * 4
+    assert elm.fit_streamed_workspace_bytes(1000, 16, 1) == elm.fit_workspace_bytes(1000, 16, 1, True)
+    assert elm.fit_streamed_workspace_bytes(1000, 513, 1, 0) == 0
 
 
 def test_no_cpu_fallback_and_no_oracle_in_the_product():
