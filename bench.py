@@ -5,12 +5,14 @@ A "step" is one whole fit (weights from the seed -> hidden matrix H(Q) -> TSQR s
 refinement) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--contraction fp32]
-                    [--no-fast-mode] [--no-cpu-baseline]
+                    [--no-fast-mode] [--no-streamed] [--no-cpu-baseline]
 
 The reported line is for --contraction (default fp32: float32 matrix instructions, the arithmetic the
 configurations name).  Unless --no-fast-mode is given, the same K steps are then timed once more
 in the library's other stage-1 mode (split16: the recurrent contraction as an fp16 hi/lo split on
-fp16 matrix instructions, float32-equivalent accuracy) and reported under "fast_mode".
+fp16 matrix instructions, float32-equivalent accuracy) and reported under "fast_mode".  Unless
+--no-streamed is given, the streamed fit (H produced and folded into the TSQR chunk by chunk, never
+stored) is timed as well and reported under "streamed_fit".
 
 Workload: the LSTM N = 4M, Q = 100, d = 8, L = 512, m = 2 configuration (the one the headline
 metric is quoted on); other configurations can be selected for study with --config.
@@ -156,6 +158,7 @@ def main() -> int:
     ap.add_argument("--contraction", default="fp32", choices=["fp32", "split16"],
                     help="stage-1 contraction mode of the reported line")
     ap.add_argument("--no-fast-mode", action="store_true", help="skip the extra split16 measurement")
+    ap.add_argument("--no-streamed", action="store_true", help="skip the extra streamed-fit measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
@@ -277,6 +280,32 @@ def main() -> int:
                             "ms_per_step": 1e3 * fdt / args.steps, "hidden_ms": f_hidden, "solve_ms": f_solve,
                             "rmse": fstats[-1].rmse, "ne_resid": fstats[-1].ne_resid,
                             "roofline": roofline("split16", f_hidden)}
+    if not args.no_streamed and args.contraction == "fp32":
+        # the same fit with H produced and folded into the TSQR chunk by chunk (never stored)
+        del H, ws
+        kw.pop("workspace"), kw.pop("H_out")
+        sws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m), dtype=torch.uint8, device="cuda")
+
+        def sstep():
+            res = elm.fit_streamed(cfg.cell, X, T, cfg.L, cfg.seed, workspace=sws, **kw)
+            st = res.stats
+            res.model.close()
+            return st
+
+        sstep()
+        torch.cuda.synchronize()
+        ssteps = min(args.steps, 2)
+        t0 = time.perf_counter()
+        sstats = [sstep() for _ in range(ssteps)]
+        torch.cuda.synchronize()
+        sdt = time.perf_counter() - t0
+        out["streamed_fit"] = {"value": cfg.N * ssteps / sdt, "unit": "samples/s", "steps": ssteps,
+                               "ms_per_step": 1e3 * sdt / ssteps,
+                               "hidden_ms": float(np.mean([s.t_hidden_ms for s in sstats])),
+                               "solve_ms": float(np.mean([s.t_solve_ms for s in sstats])),
+                               "refine_iters": sstats[-1].refine_iters, "rmse": sstats[-1].rmse,
+                               "workspace_bytes": sws.numel(),
+                               "ordinary_fit_bytes": elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, True)}
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
                                  "cfg5": 4096, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]
