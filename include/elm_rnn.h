@@ -187,10 +187,20 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
  * 128 rows and capped at N). */
 size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows);
 
-/* Algorithm "S-R-ELM" with steps (2) and (3) interleaved: only H(Q) enters step (3), and the R factor
- * of [H | T] can absorb H a block of rows at a time, so H is produced one chunk of rows at a time and
- * folded into the per-work-group R factors of the TSQR before the next chunk overwrites it.  The
- * N x L matrix never exists; the chunk buffer is small enough to stay in the memory-side cache.
+/* Algorithm "S-R-ELM" with steps (2) and (3) fused: only H(Q) enters step (3), and the R factor of
+ * [H | T] can absorb H a block of rows at a time, so the N x L matrix never exists.  Two forms:
+ *   in-kernel hand-off  the stage-1 kernel runs a persistent grid, one work-group per level-0 R factor
+ *                       of the TSQR; every finished tile [H(Q) | T] is rewritten in LDS as the next row
+ *                       block and folded into that R factor before the work-group starts its next tile.
+ *                       Exists for float32-contraction models of the dense cells whose layer is wide
+ *                       enough that stage 1 runs one work-group per compute unit (LSTM L > 128,
+ *                       Elman / GRU L > 256);
+ *   chunked             H is produced one chunk of rows at a time into a buffer small enough to stay in
+ *                       the memory-side cache and folded into the R factors by the TSQR's level 0 before
+ *                       the next chunk overwrites it.  Any cell, any contraction.
+ * chunk_rows = 0 picks the hand-off when it exists and N fills the level-0 grid (256 R factors), else
+ * default chunks; chunk_rows > 0 asks for chunks of that many rows; chunk_rows = -1 asks for the
+ * hand-off and returns ELM_EUNSUPPORTED where it does not exist.
  * Same arguments and results as elm_rnn_fit (there is no H_out), and the same beta up to float32
  * rounding in the factorisation, except:
  *   refine = 0      beta is the plain float32 TSQR solution; stats->rmse is read off the R factor
@@ -199,7 +209,8 @@ size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chu
  *                   chunk (one more run of step (2)), plus one more run for the statistics;
  *   refine = -1     refine twice if max|R_jj| > 30 min|R_jj| (the unrefined normal-equation residual is
  *                   about 1e-8 .. 6e-8 times that ratio), else not at all.
- * stats->t_hidden_ms sums every run of step (2); stats->refine_iters reports the steps taken. */
+ * stats->t_hidden_ms sums every run of step (2) (with the hand-off it includes level 0 of the TSQR);
+ * stats->refine_iters reports the steps taken. */
 int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T,
                          int64_t N, int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
                          int64_t chunk_rows, int refine, void* workspace, size_t workspace_bytes,

@@ -460,7 +460,7 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
                          void* hip_stream, float* beta_out, double* beta64_out, elm_rnn_stats* stats,
                          elm_rnn_model** model_out) {
     if (X == nullptr || T == nullptr || beta_out == nullptr || model_out == nullptr) return ELM_EINVAL;
-    if (N < 1 || N < L || refine < -1 || refine > 4 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    if (N < 1 || N < L || refine < -1 || refine > 4 || ldx_n < 0 || ldx_q < 0 || chunk_rows < -1) return ELM_EINVAL;
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
     const size_t need = elm_rnn_fit_streamed_workspace_bytes(N, L, m, chunk_rows);
@@ -509,11 +509,27 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
         return ELM_EHIP;
     };
 
+    // In-kernel hand-off (the tile goes from LDS into the fold) where stage 1 has such a variant: chosen
+    // by default when the level-0 grid of the plan fills the chip, forced by chunk_rows == -1.
+    const bool can_fuse = mdl->contraction == ELM_CONTRACT_FP32 && mdl->dWp != nullptr &&
+                          hidden_fused_available(mdl->lay, plan);
+    if (chunk_rows == -1 && !can_fuse) {
+        elm_rnn_free(mdl);
+        return ELM_EUNSUPPORTED;
+    }
+    const bool fuse = can_fuse && (chunk_rows == -1 || (chunk_rows == 0 && plan.groups[0] >= 256));
+
     hipError_t e = span.mark(stream);
-    if (e == hipSuccess)
+    if (e == hipSuccess && fuse) {
+        e = s1.mark(stream);
+        if (e == hipSuccess)
+            e = launch_hidden_fused(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q, T, plan, workspace, stream);
+        if (e == hipSuccess) e = s1.mark(stream);
+    } else if (e == hipSuccess) {
         e = sweep([&](const float* Tc, int64_t rows, bool later) {
             return launch_tsqr_level0(plan, Hc, Tc, rows, workspace, later ? 1 : 0, stream);
         });
+    }
     float* R = nullptr;
     if (e == hipSuccess) e = launch_tsqr_combine(plan, workspace, &R, stream);
     if (e == hipSuccess) e = launch_backsolve(plan, R, workspace, stream);

@@ -84,6 +84,12 @@ hipError_t launch_tsqr(const SolvePlan& plan, const float* H, const float* T, vo
 hipError_t launch_tsqr_level0(const SolvePlan& plan, const float* H, const float* T, int64_t rows, void* ws,
                               int keep, hipStream_t stream);
 hipError_t launch_tsqr_combine(const SolvePlan& plan, void* ws, float** R_final, hipStream_t stream);
+// Stage 1 and level 0 of the TSQR in one kernel (H is never stored), for the layers whose stage-1 variant
+// runs one work-group per compute unit; the R factors land where launch_tsqr_level0 would put them.
+bool hidden_fused_available(const PackedLayout& lay, const SolvePlan& plan);
+hipError_t launch_hidden_fused(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
+                               int64_t ldx_q, int64_t N, int Q, const float* T, const SolvePlan& plan,
+                               void* ws, hipStream_t stream);
 hipError_t launch_backsolve(const SolvePlan& plan, const float* R, void* ws, hipStream_t stream);
 hipError_t launch_residual_pass(const SolvePlan& plan, const float* H, const float* T, void* ws,
                                 hipStream_t stream);

@@ -86,6 +86,56 @@ def test_streamed_fit_meets_the_bars_of_the_ordinary_fit(elm, name, n, L, chunk,
     res.model.close()
 
 
+FUSED_CASES = [  # data, cell, N, L: every stage-1 variant that has the in-kernel hand-off (tile -> fold through LDS)
+    ("cfg3", "lstm", 5000, 160),      # two column chunks
+    ("cfg3", "lstm", 5001, 300),      # three chunks, two-pass with LDS staging
+    ("cfg5", "lstm", 4003, 512),      # four chunks (the headline variant)
+    ("cfg5", "elman", 4100, 320),     # three chunks (8 input channels keep the wide layer well conditioned)
+    ("cfg5", "elman", 4099, 512),     # four chunks
+    ("cfg4", "gru", 4500, 288),       # 64-row tiles
+    ("cfg4", "gru", 4501, 320),       # 32-row tiles, three chunks
+    ("cfg4", "gru", 4001, 448),       # 32-row tiles, four chunks
+]
+
+
+@pytest.mark.parametrize("name,cell,n,L", FUSED_CASES)
+def test_fused_hand_off_meets_the_bars_of_the_ordinary_fit(elm, name, cell, n, L):
+    """chunk_rows = -1: stage 1 folds every finished tile into the TSQR inside the kernel."""
+    import dataclasses
+    cfg, X, T, L = problem(name, n, L, Q=6)
+    if cell != cfg.cell:
+        cfg = dataclasses.replace(cfg, cell=cell, w_scale=0.3, spectral_radius=0.9, forget_bias=0.0, zero_bias=False)
+    Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
+    res = elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, chunk_rows=-1, **cfg_kwargs(cfg))
+    H, rmse, ne = check_against_oracle(elm, res, Xd, T)
+    assert abs(res.stats.rmse_qr - rmse) <= 1e-3 * rmse
+    # the R factor is the one the chunked path builds from the stored tiles: same diagonal range, same beta
+    alt = elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, chunk_rows=1024, **cfg_kwargs(cfg))
+    assert alt.stats.refine_iters == res.stats.refine_iters
+    assert abs(alt.stats.r_diag_min - res.stats.r_diag_min) <= 1e-3 * res.stats.r_diag_min
+    assert abs(alt.stats.r_diag_max - res.stats.r_diag_max) <= 1e-4 * res.stats.r_diag_max
+    b, a = res.beta64.cpu().numpy(), alt.beta64.cpu().numpy()
+    # both are least-squares solutions to float32 factorisation accuracy: compare the fitted values
+    Hd = H.astype(np.float64)
+    assert np.abs(Hd @ (a - b)).max() <= 1e-4 * max(np.abs(T).max(), 1.0)
+    alt.model.close()
+    res.model.close()
+
+
+def test_fused_hand_off_is_refused_where_no_variant_exists(elm):
+    cfg, X, T, L = problem("cfg3", 3000, 100)
+    Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
+    with pytest.raises(elm.ElmRnnError) as err:
+        elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, chunk_rows=-1, **cfg_kwargs(cfg))
+    assert err.value.code == -5
+    with pytest.raises(elm.ElmRnnError) as err:       # the split contraction has no fused form
+        elm.fit_streamed(cfg.cell, Xd, Td, 160, cfg.seed, chunk_rows=-1, contraction="split16", **cfg_kwargs(cfg))
+    assert err.value.code == -5
+    with pytest.raises(elm.ElmRnnError) as err:
+        elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, chunk_rows=-2, **cfg_kwargs(cfg))
+    assert err.value.code == -1
+
+
 def test_streamed_fit_is_independent_of_the_chunking(elm):
     cfg, X, T, L = problem("cfg3", 20_000, 96)
     Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
@@ -134,7 +184,7 @@ def test_streamed_fit_workspace(elm):
 
 
 def test_streamed_fit_cfg5_full_size(elm):
-    """The headline configuration at full size with the default chunking, as bench.py launches it."""
+    """The headline configuration at full size in the default mode (in-kernel hand-off), as bench.py launches it."""
     cfg = synthdata.get_config("cfg5")
     series, _, T = synthdata.make_problem(cfg, materialise=False)
     sd = torch.from_numpy(series).cuda()
