@@ -159,6 +159,10 @@ def main() -> int:
                     help="stage-1 contraction mode of the reported line")
     ap.add_argument("--no-fast-mode", action="store_true", help="skip the extra split16 measurement")
     ap.add_argument("--no-streamed", action="store_true", help="skip the extra streamed-fit measurement")
+    ap.add_argument("--streamed", action="store_true",
+                    help="time the streamed fit as the main leg (profiling runs; implies --no-streamed)")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="streamed fit: 0 = library default, -1 = in-kernel hand-off, > 0 = rows per chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
@@ -193,13 +197,23 @@ def main() -> int:
     sd = torch.from_numpy(series).cuda()
     X = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1)).contiguous()   # materialised windows
     T = sd[cfg.Q:cfg.Q + cfg.N, :cfg.m].contiguous()
-    H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
-    ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
     kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
-              zero_bias=cfg.zero_bias, workspace=ws, H_out=H)
+              zero_bias=cfg.zero_bias)
+    if args.streamed:
+        args.no_streamed = True
+        H = None
+        ws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0)),
+                         dtype=torch.uint8, device="cuda")
+    else:
+        H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
+        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
 
     def step(mode=args.contraction):
-        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, contraction=mode, **kw)
+        if args.streamed:
+            res = elm.fit_streamed(cfg.cell, X, T, cfg.L, cfg.seed, contraction=mode, chunk_rows=args.chunk_rows,
+                                   workspace=ws, **kw)
+        else:
+            res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, contraction=mode, workspace=ws, H_out=H, **kw)
         st = res.stats
         res.model.close()
         return st
@@ -262,8 +276,9 @@ def main() -> int:
                    "hidden_ms": hidden_ms, "solve_ms": solve_ms,
                    "hidden_samples_per_s": cfg.N / (hidden_ms * 1e-3),
                    "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
-                   "contraction": args.contraction,
-                   "rmse": stats[-1].rmse, "ne_resid": stats[-1].ne_resid},
+                   "contraction": args.contraction, "streamed": bool(args.streamed),
+                   "rmse": stats[-1].rmse,
+                   "ne_resid": None if np.isnan(stats[-1].ne_resid) else stats[-1].ne_resid},
         "roofline": roofline(args.contraction, hidden_ms),
     }
     if (not args.no_fast_mode and args.contraction == "fp32" and cfg.d <= 15
@@ -283,11 +298,11 @@ def main() -> int:
     if not args.no_streamed and args.contraction == "fp32":
         # the same fit with H produced and folded into the TSQR chunk by chunk (never stored)
         del H, ws
-        kw.pop("workspace"), kw.pop("H_out")
-        sws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m), dtype=torch.uint8, device="cuda")
+        sws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0)),
+                          dtype=torch.uint8, device="cuda")
 
         def sstep():
-            res = elm.fit_streamed(cfg.cell, X, T, cfg.L, cfg.seed, workspace=sws, **kw)
+            res = elm.fit_streamed(cfg.cell, X, T, cfg.L, cfg.seed, workspace=sws, chunk_rows=args.chunk_rows, **kw)
             st = res.stats
             res.model.close()
             return st
