@@ -73,6 +73,9 @@ def load_library():
     if not os.path.exists(path):
         raise ElmRnnError(ELM_EINVAL, f"{path} is missing: build it with "
                                       "`python -m paper_1911_13252_amd.build`")
+    # PyTorch ships its own HIP runtime; loading it first makes the library bind to that copy, so that the
+    # process holds one runtime (and one view of the device) whichever of the two is used first
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, i64, u64, sz, dp, fp = C.c_void_p, C.c_int64, C.c_uint64, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_float)
     lib.elm_rnn_model_create.argtypes = [C.c_int] * 5 + [u64, C.POINTER(_Init), C.POINTER(vp)]
