@@ -217,11 +217,13 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
                          void* hip_stream, float* beta_out, double* beta64_out,
                          elm_rnn_stats* stats, elm_rnn_model** model_out);
 
-/* Workspace for elm_rnn_predict: N*L floats for H. */
+/* Workspace with which elm_rnn_predict runs in one pass: N*L floats for H. */
 size_t elm_rnn_predict_workspace_bytes(int64_t N, int L);
 
 /* The paper's output equation y_hat = sum_i beta_i f_i(Q): build H(Q) for N new windows with
- * the model's weights and write Y_out = H beta (device, N x m float32). */
+ * the model's weights and write Y_out = H beta (device, N x m float32).  A smaller workspace is
+ * accepted as long as it holds 256 rows of H (or all N): H is then produced and consumed in chunks of as
+ * many rows as fit, with the same result. */
 int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
                     int64_t N, float* Y_out, void* workspace, size_t workspace_bytes,
                     void* hip_stream);

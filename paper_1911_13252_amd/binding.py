@@ -368,8 +368,8 @@ def predict(model: Model, X, workspace=None, stream=None):
     if d != model.d or Q < model.Q:
         raise ValueError("X does not match the model")
     ldn, ldq = _x_strides(X)
-    need = int(lib.elm_rnn_predict_workspace_bytes(N, model.L))
-    if workspace is None:
+    if workspace is None:      # one pass when H is small, else chunks of about 128 MiB of H
+        need = min(int(lib.elm_rnn_predict_workspace_bytes(N, model.L)), 128 << 20)
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     Y = torch.empty((N, model.m), dtype=torch.float32, device=X.device)
     _check(lib.elm_rnn_predict(model._h, X.data_ptr(), ldn, ldq, N, Y.data_ptr(), workspace.data_ptr(),

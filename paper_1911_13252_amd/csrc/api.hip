@@ -600,13 +600,20 @@ size_t elm_rnn_predict_workspace_bytes(int64_t N, int L) {
 int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
                     int64_t N, float* Y_out, void* workspace, size_t workspace_bytes,
                     void* hip_stream) {
-    if (model == nullptr || X == nullptr || Y_out == nullptr || N < 1) return ELM_EINVAL;
-    if (workspace == nullptr || workspace_bytes < elm_rnn_predict_workspace_bytes(N, model->L))
-        return ELM_EWORKSPACE;
+    if (model == nullptr || X == nullptr || Y_out == nullptr || N < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    if (workspace == nullptr) return ELM_EWORKSPACE;
+    // H is produced and consumed in chunks of as many rows as the workspace holds (whole groups of 256)
+    int64_t chunk = (int64_t)(workspace_bytes / ((size_t)model->L * sizeof(float)));
+    if (chunk < N) chunk = chunk / 256 * 256;
+    if (chunk < 1) return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float* H = static_cast<float*>(workspace);
-    ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, model->Q, nullptr, nullptr, H, nullptr, stream));
-    ELM_HIP_TRY(launch_predict_gemv(H, model->dBeta, N, model->L, model->m, Y_out, stream));
+    for (int64_t r0 = 0; r0 < N; r0 += chunk) {
+        const int64_t rows = (N - r0 < chunk) ? N - r0 : chunk;
+        ELM_HIP_TRY(run_hidden(model, X + r0 * ldx_n, ldx_n, ldx_q, rows, model->Q, nullptr, nullptr, H, nullptr,
+                               stream));
+        ELM_HIP_TRY(launch_predict_gemv(H, model->dBeta, rows, model->L, model->m, Y_out + r0 * model->m, stream));
+    }
     return ELM_OK;
 }
 

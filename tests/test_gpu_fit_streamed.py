@@ -213,3 +213,21 @@ def test_streamed_fit_cfg5_full_size(elm):
     assert abs(res.stats.rmse - rmse) <= 1e-4 * rmse
     assert rmse < 1.0
     res.model.close()
+
+
+def test_predict_through_a_small_workspace(elm):
+    """elm_rnn_predict chunks H through whatever workspace it is given: same Y, bit for bit."""
+    cfg, X, T, L = problem("cfg3", 10_000, 96)
+    Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
+    res = elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, **cfg_kwargs(cfg))
+    Y = elm.predict(res.model, Xd)
+    for rows in (256, 1000, 4096):
+        ws = torch.empty(rows * L * 4, dtype=torch.uint8, device="cuda")
+        assert torch.equal(elm.predict(res.model, Xd, workspace=ws), Y)
+    H = elm.hidden(res.model, Xd).double()
+    ref = (H @ res.beta64).cpu().numpy()
+    np.testing.assert_allclose(Y.cpu().numpy(), ref, atol=2e-5 * max(1.0, np.abs(T).max()))
+    with pytest.raises(elm.ElmRnnError) as err:
+        elm.predict(res.model, Xd, workspace=torch.empty(255 * L * 4, dtype=torch.uint8, device="cuda"))
+    assert err.value.code == -2
+    res.model.close()
