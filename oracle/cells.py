@@ -113,8 +113,11 @@ def hidden_elman_diag(X, W, alpha, b, steps=None):
     hist = np.zeros((steps + 1, N, L))           # hist[t] = h(t), hist[0] unused (no state before t = 1)
     for t in range(1, steps + 1):
         a = X[:, t - 1, :] @ W + b
-        for k in range(1, t):
-            a = a + alpha[:, k - 1] * hist[t - k]
+        if t > 1:
+            # sum over the lags k = 1..t-1 of alpha[j, k-1] * h_j(t-k), taken in one array contraction:
+            # past[k-1] = h(t-k)
+            past = hist[t - 1:0:-1]
+            a = a + np.einsum("knl,lk->nl", past, alpha[:, :t - 1])
         hist[t] = np.tanh(a)
     return hist[steps] if steps > 0 else np.zeros((N, L))
 
