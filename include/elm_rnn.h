@@ -51,7 +51,7 @@ extern "C" {
 #define ELM_CELL_ELMAN_DIAG 3 /* the paper's section "Elman" as printed (Eq. hij_elman): neuron j feeds
                                 back on itself only, from every earlier step of the window:
                                 h_j(t) = tanh(x(t) W[:,j] + b_j + sum_{k=1}^{t-1} alpha[j][k-1] h_j(t-k));
-                                its recurrent array "U" is alpha, L x Q (lag k in column k-1), Q <= 512;
+                                its recurrent array "U" is alpha, L x Q (lag k in column k-1), Q <= 4096;
                                 no initial state can be passed and Q_run <= Q                        */
 
 #define ELM_CELL_FC_MULTILAG 4 /* the paper's section "Fully Connected RNN" (Eq. hij_fc): every neuron is fed

@@ -10,7 +10,9 @@
 // A work-group of four waves walks over the neurons of its 64-sample tile; the tile's windows are
 // staged once in LDS (transposed, coalesced global reads) and results leave through an LDS tile
 // so that H is written in 128-byte row segments.  Windows too large for LDS are read directly.
-// Q above 64 takes a one-wave kernel that keeps the history in LDS.
+// Q above 64 takes a one-wave kernel that keeps the history in LDS; Q above 512 (the paper's longest
+// windows have 3,197 steps) a kernel that spreads the time axis of one (sample, neuron) pair over the
+// lanes of a wave instead.
 
 #include "internal.h"
 
@@ -162,6 +164,105 @@ __global__ __launch_bounds__(64) void diag_lds_kernel(
     }
 }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Long windows (Q <= 64*SLOTS).  A wave owns SPW (sample, neuron) pairs of one neuron; lane l, slot i of
+// `hist` belongs to step tau = 64 i + l (counted from 0).  Before step tau is taken the entry holds the
+// input part u(tau) = x(tau) W[:, j] + b_j, afterwards h(tau).  The feedback sum of step tau is a dot
+// product over all lanes and slots with the lag weights read from LDS at index OFF + tau - tau': the
+// table is zero at and below OFF, so entries of steps not yet taken (tau' >= tau) drop out by themselves
+// and the sum is one wavefront reduction per step.  Q(Q-1)/2 fused multiply-adds per pair, as the cell
+// defines it; the four waves of a work-group share the neuron, hence the lag table.
+template <int SLOTS>
+__global__ __launch_bounds__(256) void diag_long_kernel(
+    const float* __restrict__ X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
+    const float* __restrict__ Wt, const float* __restrict__ alpha, const float* __restrict__ bias,
+    int lda, float* __restrict__ H) {
+    constexpr int SPW = 2;
+    constexpr int OFF = 64 * SLOTS;
+    extern __shared__ float P[];                  // [OFF + Q]: P[OFF + k] = alpha[j][k-1], k = 1..Q-1
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = blockIdx.y;
+    for (int idx = threadIdx.x; idx < OFF + Q; idx += 256) {
+        const int k = idx - OFF;
+        P[idx] = (k >= 1 && k <= Q - 1) ? alpha[(size_t)j * lda + (k - 1)] : 0.0f;
+    }
+    __syncthreads();
+
+    const int64_t i0 = ((int64_t)blockIdx.x * 4 + wave) * SPW;
+    const float bj = bias[j];
+    float hist[SPW][SLOTS];
+#pragma unroll
+    for (int s = 0; s < SPW; ++s) {
+        const int64_t irow = i0 + s < N ? i0 + s : N - 1;        // tail pairs repeat the last row
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            const int tau = 64 * i + lane;
+            float a = 0.0f;
+            if (tau < Q) {
+                a = bj;
+                for (int c = 0; c < d; ++c) a = fmaf(load_x(X, ldx_n, ldx_q, irow, tau, c), Wt[(size_t)j * d + c], a);
+            }
+            hist[s][i] = a;
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        if (64 * i < Q) {                         // uniform
+            const int tend = min(64, Q - 64 * i);
+            for (int tt = 0; tt < tend; ++tt) {
+                const float* pp = P + OFF + 64 * i + tt - lane;
+                float acc[SPW];
+#pragma unroll
+                for (int s = 0; s < SPW; ++s) acc[s] = 0.0f;
+#pragma unroll
+                for (int ip = 0; ip <= i; ++ip) {
+                    const float pv = pp[-64 * ip];
+#pragma unroll
+                    for (int s = 0; s < SPW; ++s) acc[s] = fmaf(pv, hist[s][ip], acc[s]);
+                }
+#pragma unroll
+                for (int s = 0; s < SPW; ++s) {
+                    const float fb = wave_sum(acc[s]);
+                    const float u = __builtin_bit_cast(
+                        float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hist[s][i]), tt));
+                    const float h = tanh_d(u + fb);
+                    hist[s][i] = (lane == tt) ? h : hist[s][i];
+                }
+            }
+        }
+    }
+
+    // h(Q - 1) sits in lane (Q-1) % 64 of slot (Q-1) / 64
+    const int qi = (Q - 1) >> 6, ql = (Q - 1) & 63;
+#pragma unroll
+    for (int s = 0; s < SPW; ++s) {
+        float v = 0.0f;
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) v = (i == qi) ? hist[s][i] : v;
+        v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), ql));
+        if (lane == 0 && i0 + s < N) H[(size_t)(i0 + s) * L + j] = v;
+    }
+}
+
+template <int SLOTS>
+hipError_t launch_long(const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
+                       const float* Wt, const float* alpha, const float* bias, int lda, float* H,
+                       hipStream_t stream) {
+    const int64_t groups = (N + 7) / 8;           // 4 waves x 2 samples per work-group
+    if (groups > 0x7fffffff || L > 65535) return hipErrorInvalidValue;
+    const size_t lds = (size_t)(64 * SLOTS + Q) * sizeof(float);
+    diag_long_kernel<SLOTS><<<dim3((unsigned)groups, (unsigned)L), 256, lds, stream>>>(
+        X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+    return hipGetLastError();
+}
+
 template <int QMAX, int JT>
 hipError_t launch_reg(const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
                       const float* Wt, const float* alpha, const float* bias, int lda, float* H,
@@ -202,6 +303,9 @@ hipError_t launch_hidden_diag(const float* Wt, const float* alpha, const float* 
     if (Q <= 16) return launch_reg<16, 4>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
     if (Q <= 32) return launch_reg<32, 2>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
     if (Q <= 64) return launch_reg<64, 1>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
+    if (Q > 2048) return launch_long<64>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
+    if (Q > 1024) return launch_long<32>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
+    if (Q > 512) return launch_long<16>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
     const size_t hs_bytes = (size_t)Q * 64 * sizeof(float);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(diag_lds_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)hs_bytes);

@@ -59,7 +59,7 @@ hipError_t launch_hidden_split(const SplitLayout& lay, const void* Wp, const flo
 
 // The paper's own Elman cell (diagonal, multi-lag feedback).  Wt is W transposed [L][d], alpha is
 // [L][lda] with lag k in column k-1, Q <= lda steps are run.
-constexpr int kDiagMaxQ = 512;
+constexpr int kDiagMaxQ = 4096;
 hipError_t launch_hidden_diag(const float* Wt, const float* alpha, const float* bias, int lda,
                               const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
                               float* H, hipStream_t stream);

@@ -33,6 +33,10 @@ def weights(Q, d, L, seed):
     (150, 40, 16, 12),      # 640 window elements per sample: past the LDS tile, read directly
     (129, 12, 64, 9),       # widest input
     (5000, 10, 1, 512),     # largest L, neurons split over the second grid dimension
+    # long windows (time axis spread over the lanes of a wave): 16, 32 and 64 register slots per lane at
+    # and next to their limits, odd and even sample counts, the paper's longest window (3,197 steps)
+    (9, 513, 1, 3), (17, 1024, 2, 5), (8, 1025, 1, 2), (23, 2048, 1, 3), (11, 2049, 3, 2), (20, 3197, 1, 4),
+    (5, 4096, 1, 2),
 ])
 def test_hidden_matches_oracle(elm, N, Q, d, L):
     W, alpha, b = weights(Q, d, L, seed=N + Q + L)
@@ -56,6 +60,21 @@ def test_fewer_steps_and_sliding_windows_without_copy(elm):
     for q in (1, 7, 16, 23):
         got = elm.hidden(model, Xview, Q_run=q).cpu().numpy()
         assert h_close(got, ocells.hidden_elman_diag(Xh, W, alpha, b, steps=q)), q
+    model.close()
+
+
+def test_long_window_model_run_for_fewer_steps(elm):
+    """A 3,197-step model unrolled for fewer steps goes through every kernel family of the cell."""
+    Q, d, L, N = 3197, 1, 3, 37
+    W, alpha, b = weights(Q, d, L, seed=11)
+    alpha *= 40.0                                  # the early lags matter at short horizons too
+    alpha[:, 60:] /= 40.0
+    X = np.random.default_rng(12).uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    model = elm.Model.from_weights("elman_diag", Q, 1, W, alpha, b)
+    for q in (5, 64, 65, 512, 513, 1500, 3000, 3197):
+        got = elm.hidden(model, Xd, Q_run=q).cpu().numpy()
+        assert h_close(got, ocells.hidden_elman_diag(X, W, alpha, b, steps=q)), q
     model.close()
 
 
@@ -113,5 +132,5 @@ def test_argument_errors(elm):
     assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 12, 2, 5, 7, None, None, H.data_ptr(), None, None) == -1
     model.close()
     with pytest.raises(elm.ElmRnnError) as ei:
-        elm.Model.create("elman_diag", 513, 1, 4, 1, seed=1)
+        elm.Model.create("elman_diag", 4097, 1, 4, 1, seed=1)
     assert ei.value.code == -5

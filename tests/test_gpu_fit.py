@@ -118,9 +118,10 @@ def test_fit_gated_configs_properties(elm, name, N, mode):
 
 
 @pytest.mark.parametrize("mode", MODES)
-def test_fit_cfg5_full_size(elm, mode):
-    """The headline configuration at full size, as bench.py launches it (materialised windows)."""
-    cfg = synthdata.get_config("cfg5")
+@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+def test_fit_full_size(elm, name, mode):
+    """The two largest configurations at full size, as bench.py launches them (materialised windows)."""
+    cfg = synthdata.get_config(name)
     series, _, T = synthdata.make_problem(cfg, materialise=False)
     sd = torch.from_numpy(series).cuda()
     Xd = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1)).contiguous()
