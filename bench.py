@@ -128,6 +128,15 @@ def run_sweep(elm, torch, steps: int) -> dict:
             r = timed_fit(b, X, T, mode)
             r["study"] = "long windows"
             rows.append(r)
+    # the paper's own Elman cell on that shape (Q(Q-1)/2 lag terms per sample and neuron); its widest layer
+    # there is 100 units.  The weight scale shrinks with sqrt(Q) so that the feedback sum keeps its size.
+    for L in (50, 100):
+        b = dataclasses.replace(base["elman_diag"], N=4500, Q=3197, L=L, w_scale=0.3 * (50 / 3197) ** 0.5)
+        X, T = windows(b)
+        r = timed_fit(b, X, T, "fp32")
+        r["study"] = "long windows"
+        r["stage1_tflops"] = 4500 * L * (3197 * 3196 + 2 * 3197) / (r["hidden_ms"] * 1e-3) / 1e12
+        rows.append(r)
     # fit on the first 80 % of the windows, predict the last 20 %
     cfg = synthdata.get_config("cfg3")
     X, T = windows(cfg)

@@ -164,27 +164,76 @@ __global__ __launch_bounds__(64) void diag_lds_kernel(
     }
 }
 
+// Sum over the 64 lanes, returned in every lane.  Inside a row of 16 lanes the partial sums move
+// through the data-parallel lane permutations of the vector ALU (two quad swaps, two row rotations:
+// a few cycles each, no trip through the LDS crossbar); the four row sums are then read through scalar
+// registers.  This chain sits on the critical path of every step of the long-window kernel.
+template <int CTRL>
+__device__ __forceinline__ float add_dpp(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+__device__ __forceinline__ float lane_value(float v, int src) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    v = add_dpp<0xB1>(v);        // quad_perm [1,0,3,2]: lanes 1 apart
+    v = add_dpp<0x4E>(v);        // quad_perm [2,3,0,1]: lanes 2 apart
+    v = add_dpp<0x124>(v);       // row_ror 4
+    v = add_dpp<0x128>(v);       // row_ror 8: every lane of a row holds the row's sum
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
-// Long windows (Q <= 64*SLOTS).  A wave owns SPW (sample, neuron) pairs of one neuron; lane l, slot i of
-// `hist` belongs to step tau = 64 i + l (counted from 0).  Before step tau is taken the entry holds the
+// The steps of slot I (64 I .. 64 I + 63) of the long-window kernel below, then those of the later slots:
+// template recursion, so that every index into the history registers is a compile-time constant.
+template <int I, int SLOTS, int SPW>
+struct LongSlots {
+    static constexpr int OFF = 64 * SLOTS;
+    static __device__ __forceinline__ void run(float (&hist)[SPW][SLOTS], const float* P, int Q, int lane) {
+        if (64 * I >= Q) return;                  // uniform
+        const int tend = min(64, Q - 64 * I);
+        for (int tt = 0; tt < tend; ++tt) {
+            const float* pp = P + OFF + 64 * I + tt - lane;
+            float acc[SPW];
+#pragma unroll
+            for (int s = 0; s < SPW; ++s) acc[s] = 0.0f;
+#pragma unroll
+            for (int ip = 0; ip <= I; ++ip) {
+                const float pv = pp[-64 * ip];
+#pragma unroll
+                for (int s = 0; s < SPW; ++s) acc[s] = fmaf(pv, hist[s][ip], acc[s]);
+            }
+#pragma unroll
+            for (int s = 0; s < SPW; ++s) {
+                const float h = tanh_d(lane_value(hist[s][I], tt) + wave_sum(acc[s]));
+                hist[s][I] = (lane == tt) ? h : hist[s][I];
+            }
+        }
+        LongSlots<I + 1, SLOTS, SPW>::run(hist, P, Q, lane);
+    }
+};
+template <int SLOTS, int SPW>
+struct LongSlots<SLOTS, SLOTS, SPW> {
+    static __device__ __forceinline__ void run(float (&)[SPW][SLOTS], const float*, int, int) {}
+};
+
+// Long windows (Q <= 64*SLOTS).  A wave owns SPW = 2 (sample, neuron) pairs of one neuron; lane l, slot i
+// of `hist` belongs to step tau = 64 i + l (counted from 0).  Before step tau is taken the entry holds the
 // input part u(tau) = x(tau) W[:, j] + b_j, afterwards h(tau).  The feedback sum of step tau is a dot
 // product over all lanes and slots with the lag weights read from LDS at index OFF + tau - tau': the
 // table is zero at and below OFF, so entries of steps not yet taken (tau' >= tau) drop out by themselves
-// and the sum is one wavefront reduction per step.  Q(Q-1)/2 fused multiply-adds per pair, as the cell
-// defines it; the four waves of a work-group share the neuron, hence the lag table.
+// and the sum is one wavefront reduction per step and pair.  Q(Q-1)/2 multiply-adds per pair, as the cell
+// defines it.  A step is a dependent chain (table reads, multiply-adds, reduction, tanh, write-back), so
+// the rate comes from the number of waves a SIMD can interleave: the history registers (2 x SLOTS) are
+// sized to the window.  The four waves of a work-group share the neuron, hence the lag table.
 template <int SLOTS>
-__global__ __launch_bounds__(256) void diag_long_kernel(
+__device__ __forceinline__ void diag_long_body(
     const float* __restrict__ X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
     const float* __restrict__ Wt, const float* __restrict__ alpha, const float* __restrict__ bias,
     int lda, float* __restrict__ H) {
     constexpr int SPW = 2;
     constexpr int OFF = 64 * SLOTS;
-    extern __shared__ float P[];                  // [OFF + Q]: P[OFF + k] = alpha[j][k-1], k = 1..Q-1
+    extern __shared__ float P[];                  // [OFF + Q]: P[OFF + k] = alpha[j][k-1], k = 1..Q-1, else 0
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
@@ -212,32 +261,7 @@ __global__ __launch_bounds__(256) void diag_long_kernel(
         }
     }
 
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        if (64 * i < Q) {                         // uniform
-            const int tend = min(64, Q - 64 * i);
-            for (int tt = 0; tt < tend; ++tt) {
-                const float* pp = P + OFF + 64 * i + tt - lane;
-                float acc[SPW];
-#pragma unroll
-                for (int s = 0; s < SPW; ++s) acc[s] = 0.0f;
-#pragma unroll
-                for (int ip = 0; ip <= i; ++ip) {
-                    const float pv = pp[-64 * ip];
-#pragma unroll
-                    for (int s = 0; s < SPW; ++s) acc[s] = fmaf(pv, hist[s][ip], acc[s]);
-                }
-#pragma unroll
-                for (int s = 0; s < SPW; ++s) {
-                    const float fb = wave_sum(acc[s]);
-                    const float u = __builtin_bit_cast(
-                        float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hist[s][i]), tt));
-                    const float h = tanh_d(u + fb);
-                    hist[s][i] = (lane == tt) ? h : hist[s][i];
-                }
-            }
-        }
-    }
+    LongSlots<0, SLOTS, SPW>::run(hist, P, Q, lane);
 
     // h(Q - 1) sits in lane (Q-1) % 64 of slot (Q-1) / 64
     const int qi = (Q - 1) >> 6, ql = (Q - 1) & 63;
@@ -246,10 +270,29 @@ __global__ __launch_bounds__(256) void diag_long_kernel(
         float v = 0.0f;
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) v = (i == qi) ? hist[s][i] : v;
-        v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), ql));
+        v = lane_value(v, ql);
         if (lane == 0 && i0 + s < N) H[(size_t)(i0 + s) * L + j] = v;
     }
 }
+
+#define ELM_DIAG_LONG_ARGS                                                                              \
+    const float *__restrict__ X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,              \
+        const float *__restrict__ Wt, const float *__restrict__ alpha, const float *__restrict__ bias, int lda, \
+        float *__restrict__ H
+__global__ __launch_bounds__(256) void diag_long16_kernel(ELM_DIAG_LONG_ARGS) {
+    diag_long_body<16>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+}
+__global__ __launch_bounds__(256) void diag_long32_kernel(ELM_DIAG_LONG_ARGS) {
+    diag_long_body<32>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+}
+// the paper's longest windows (3,197 steps)
+__global__ __launch_bounds__(256) void diag_long52_kernel(ELM_DIAG_LONG_ARGS) {
+    diag_long_body<52>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+}
+__global__ __launch_bounds__(256) void diag_long64_kernel(ELM_DIAG_LONG_ARGS) {
+    diag_long_body<64>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+}
+#undef ELM_DIAG_LONG_ARGS
 
 template <int SLOTS>
 hipError_t launch_long(const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q, int d, int L,
@@ -258,8 +301,10 @@ hipError_t launch_long(const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, 
     const int64_t groups = (N + 7) / 8;           // 4 waves x 2 samples per work-group
     if (groups > 0x7fffffff || L > 65535) return hipErrorInvalidValue;
     const size_t lds = (size_t)(64 * SLOTS + Q) * sizeof(float);
-    diag_long_kernel<SLOTS><<<dim3((unsigned)groups, (unsigned)L), 256, lds, stream>>>(
-        X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H);
+    auto kern = SLOTS == 16 ? diag_long16_kernel : SLOTS == 32 ? diag_long32_kernel
+              : SLOTS == 52 ? diag_long52_kernel : diag_long64_kernel;
+    kern<<<dim3((unsigned)groups, (unsigned)L), 256, lds, stream>>>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias,
+                                                                    lda, H);
     return hipGetLastError();
 }
 
@@ -303,7 +348,8 @@ hipError_t launch_hidden_diag(const float* Wt, const float* alpha, const float* 
     if (Q <= 16) return launch_reg<16, 4>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
     if (Q <= 32) return launch_reg<32, 2>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
     if (Q <= 64) return launch_reg<64, 1>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, grid, jchunk, stream);
-    if (Q > 2048) return launch_long<64>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
+    if (Q > 3328) return launch_long<64>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
+    if (Q > 2048) return launch_long<52>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
     if (Q > 1024) return launch_long<32>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
     if (Q > 512) return launch_long<16>(X, ldx_n, ldx_q, N, Q, d, L, Wt, alpha, bias, lda, H, stream);
     const size_t hs_bytes = (size_t)Q * 64 * sizeof(float);
