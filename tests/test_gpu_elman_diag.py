@@ -25,7 +25,7 @@ def weights(Q, d, L, seed):
 
 
 # every unrolled variant (8, 16, 32, 64 steps) at and next to its limits, the LDS-history kernel
-# above 64 steps, ragged sample and neuron tails, windows staged in LDS and read directly
+# from 65 to 128 steps, ragged sample and neuron tails, windows staged in LDS and read directly
 @pytest.mark.parametrize("N,Q,d,L", [
     (1, 1, 1, 1), (63, 2, 3, 31), (64, 8, 1, 32), (65, 9, 2, 33), (200, 16, 4, 100), (130, 17, 1, 7),
     (1000, 20, 1, 50), (257, 32, 2, 64), (100, 33, 1, 40), (300, 50, 3, 20), (70, 64, 1, 36),
@@ -35,7 +35,7 @@ def weights(Q, d, L, seed):
     (5000, 10, 1, 512),     # largest L, neurons split over the second grid dimension
     # long windows (time axis spread over the lanes of a wave): 16, 32 and 64 register slots per lane at
     # and next to their limits, odd and even sample counts, the paper's longest window (3,197 steps)
-    (9, 513, 1, 3), (17, 1024, 2, 5), (8, 1025, 1, 2), (23, 2048, 1, 3), (11, 2049, 3, 2), (20, 3197, 1, 4),
+    (70, 128, 1, 6), (33, 129, 2, 7), (50, 300, 1, 5), (9, 513, 1, 3), (17, 1024, 2, 5), (8, 1025, 1, 2), (23, 2048, 1, 3), (11, 2049, 3, 2), (20, 3197, 1, 4),
     (5, 4096, 1, 2),
 ])
 def test_hidden_matches_oracle(elm, N, Q, d, L):
@@ -72,7 +72,7 @@ def test_long_window_model_run_for_fewer_steps(elm):
     X = np.random.default_rng(12).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     Xd = torch.from_numpy(X).cuda()
     model = elm.Model.from_weights("elman_diag", Q, 1, W, alpha, b)
-    for q in (5, 64, 65, 512, 513, 1500, 3000, 3197):
+    for q in (5, 64, 65, 128, 129, 513, 1500, 3000, 3197):
         got = elm.hidden(model, Xd, Q_run=q).cpu().numpy()
         assert h_close(got, ocells.hidden_elman_diag(X, W, alpha, b, steps=q)), q
     model.close()
