@@ -477,16 +477,32 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
     if (rc != ELM_OK) return rc;
 
     // one event pair around every stage-1 launch: their sum is the stage-1 time, the rest of the
-    // span is stage 2
+    // span is stage 2.  The pairs are summed (after a stream synchronisation) and reused every 64 chunks,
+    // so that a fit in many small chunks does not pile up events.
     struct Events {
         std::vector<hipEvent_t> ev;
+        size_t used = 0;
+        double sum_ms = 0.0;
         ~Events() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
         hipError_t mark(hipStream_t s) {
-            hipEvent_t e = nullptr;
-            hipError_t rc = hipEventCreate(&e);
-            if (rc != hipSuccess) return rc;
-            ev.push_back(e);
-            return hipEventRecord(e, s);
+            if (used == ev.size()) {
+                hipEvent_t e = nullptr;
+                hipError_t rc = hipEventCreate(&e);
+                if (rc != hipSuccess) return rc;
+                ev.push_back(e);
+            }
+            return hipEventRecord(ev[used++], s);
+        }
+        // adds the elapsed time of the recorded pairs to sum_ms; the events can then be recorded again
+        hipError_t collect(hipStream_t s) {
+            hipError_t rc = hipStreamSynchronize(s);
+            for (size_t i = 0; rc == hipSuccess && i + 1 < used; i += 2) {
+                float ms = 0.0f;
+                rc = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+                sum_ms += ms;
+            }
+            used = 0;
+            return rc;
         }
     } span, s1;
 
@@ -494,7 +510,8 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
     auto sweep = [&](auto&& consume) -> hipError_t {
         for (int64_t r0 = 0; r0 < N; r0 += chunk) {
             const int64_t rows = (N - r0 < chunk) ? N - r0 : chunk;
-            hipError_t e = s1.mark(stream);
+            hipError_t e = (s1.used >= 128) ? s1.collect(stream) : hipSuccess;
+            if (e == hipSuccess) e = s1.mark(stream);
             if (e == hipSuccess)
                 e = run_hidden(mdl, X + r0 * ldx_n, ldx_n, ldx_q, rows, Q, nullptr, nullptr, Hc, nullptr, stream);
             if (e == hipSuccess) e = s1.mark(stream);
@@ -564,14 +581,10 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
 
     if (stats != nullptr) {
         float total = 0.0f;
-        double hidden = 0.0;
         e = hipEventElapsedTime(&total, span.ev[0], span.ev[1]);
-        for (size_t i = 0; e == hipSuccess && i + 1 < s1.ev.size(); i += 2) {
-            float ms = 0.0f;
-            e = hipEventElapsedTime(&ms, s1.ev[i], s1.ev[i + 1]);
-            hidden += ms;
-        }
+        if (e == hipSuccess) e = s1.collect(stream);
         if (e != hipSuccess) return fail(e, "streamed fit: timing");
+        const double hidden = s1.sum_ms;
         const double nm = (double)N * m;
         stats->t_hidden_ms = hidden;
         stats->t_solve_ms = total - hidden;
