@@ -24,7 +24,9 @@ def main() -> None:
     out = {}
     for cell, L, kw in (("elman", 4, dict(w_scale=1.0, spectral_radius=0.9)),
                         ("lstm", 3, dict(w_scale=0.5, forget_bias=1.0)),
-                        ("gru", 3, dict(w_scale=0.5, zero_bias=True))):
+                        ("gru", 3, dict(w_scale=0.5, zero_bias=True)),
+                        ("elman_diag", 3, dict(w_scale=0.5)),
+                        ("fc_multilag", 3, dict(w_scale=0.3))):
         rng = np.random.default_rng([1911, 13252, L])
         N, Q, d, m = 12, 4, 2, 2
         X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)

@@ -24,7 +24,7 @@ def test_splitmix64_vectors_file():
         assert int(oweights.splitmix64(seed, idx + 1)[idx]) == val
 
 
-@pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
+@pytest.mark.parametrize("cell", ["elman", "lstm", "gru", "elman_diag", "fc_multilag"])
 def test_oracle_reproduces_stored_values(cell):
     g = load()[cell]
     X, T = np.array(g["X"], np.float32), np.array(g["T"], np.float32)
@@ -37,7 +37,7 @@ def test_oracle_reproduces_stored_values(cell):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("cell", ["elman", "lstm", "gru"])
+@pytest.mark.parametrize("cell", ["elman", "lstm", "gru", "elman_diag", "fc_multilag"])
 def test_hip_path_matches_stored_values(elm, cell):
     import torch
     g = load()[cell]
