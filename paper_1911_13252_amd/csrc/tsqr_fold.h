@@ -106,11 +106,12 @@ __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, in
             // branch-free update: lanes j > k apply the reflector, lane j == k stores it
             const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
             rdv[k] = (j == k) ? alpha : rdv[k] - w;
-            // one multiply-add for both roles: the reflector's own column (xk == pv there) becomes
-            // pv + pv (f - 1) = pv f, every column right of it pv - xk f w, the columns left of it keep pv (w = 0)
-            const float cf = (j == k) ? (f - 1.0f) : -(f * w);
+            // one select and one multiply-add for both roles: the reflector's own column becomes xk f
+            // (exactly rounded: the stored reflector must not lose digits), every column right of it
+            // pv - xk f w, the columns left of it keep pv (w = 0)
+            const float cf = (j == k) ? f : -(f * w);
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, pv[i]);
+            for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, (j == k) ? 0.0f : pv[i]);
             if (g == 0) {
                 if (j == k) taus[k] = tau;
                 if (j < k) Gs[j * kGs + k] = f * sj;      // v_j . v_k for the finished reflector j
