@@ -69,3 +69,53 @@ def test_random_shape(elm, seed):
     ok, worst = h_close(H, ocells.hidden_chunked(cell, X, W, U, b))
     assert ok, (cell, N, Q, d, L, mode, worst)
     model.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_long_window_of_the_papers_elman_cell(elm, seed):
+    """Window lengths across the slot counts of the long-window kernel (129 .. 4096 steps)."""
+    rng = np.random.default_rng(2000 + seed)
+    Q = int(rng.choice([rng.integers(129, 600), rng.integers(600, 1100), rng.integers(1100, 2100),
+                        rng.integers(2100, 3400), rng.integers(3400, 4097)]))
+    N, L, d = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(1, 4))
+    W, alpha, b = make_weights(rng, "elman_diag", Q, d, L)
+    alpha[:, :30] *= np.float32(20.0)                       # recent lags dominate, all count
+    alpha *= np.float32(0.9 / np.abs(alpha).sum(axis=1).max())
+    X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    q_run = int(rng.integers(1, Q + 1)) if seed % 2 else Q
+    print(f"case: N={N} Q={Q} d={d} L={L} q_run={q_run}", flush=True)
+    model = elm.Model.from_weights("elman_diag", Q, 1, W, alpha, b)
+    H = elm.hidden(model, torch.from_numpy(X).cuda(), Q_run=q_run).cpu().numpy()
+    ok, worst = h_close(H, ocells.hidden_elman_diag(X, W, alpha, b, steps=q_run))
+    assert ok, (N, Q, d, L, q_run, worst)
+    model.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_streamed_fit(elm, seed):
+    """The streamed fit on random shapes, chunk sizes and forms (in-kernel hand-off where it exists)."""
+    from oracle import lstsq
+    rng = np.random.default_rng(3000 + seed)
+    cell = str(rng.choice(["elman", "lstm", "gru"]))
+    wide = {"elman": 257, "lstm": 129, "gru": 257}[cell]
+    L = int(rng.choice([rng.integers(4, 100), rng.integers(wide, 513)]))
+    d, m, Q = int(rng.integers(3, 9)), int(rng.integers(1, 4)), int(rng.integers(2, 6))
+    N = int(rng.integers(6 * L, 6 * L + 3000))
+    hand_off = L >= wide and rng.random() < 0.6
+    chunk = -1 if hand_off else int(rng.choice([0, rng.integers(128, 2000)]))
+    mode = "split16" if (not hand_off and rng.random() < 0.4) else "fp32"
+    X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    T = (np.tanh(X[:, -1, :m] * 2.0) + 0.1 * rng.standard_normal((N, m))).astype(np.float32)
+    kw = dict(w_scale=0.4, spectral_radius=0.9 if cell == "elman" else 0.0, forget_bias=1.0 if cell == "lstm" else 0.0)
+    print(f"case: cell={cell} N={N} Q={Q} d={d} L={L} m={m} chunk={chunk} mode={mode}", flush=True)
+    Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
+    res = elm.fit_streamed(cell, Xd, Td, L, 77 + seed, chunk_rows=chunk, contraction=mode, **kw)
+    H = elm.hidden(res.model, Xd).cpu().numpy()
+    b64 = res.beta64.cpu().numpy()
+    _, ref_rss, _ = lstsq.solve(H, T)
+    ref_rmse = lstsq.rmse_from_rss(ref_rss, N, m)
+    rmse = float(np.sqrt(np.mean((H.astype(np.float64) @ b64 - T) ** 2)))
+    assert abs(rmse - ref_rmse) <= 1e-4 * ref_rmse, (rmse, ref_rmse)
+    ne = lstsq.normal_equation_residual(H, T, b64)
+    assert ne <= 1e-5, (ne, res.stats.refine_iters, res.stats.r_diag_min, res.stats.r_diag_max)
+    res.model.close()
