@@ -5,7 +5,7 @@ A "step" is one whole fit (weights from the seed -> hidden matrix H(Q) -> TSQR s
 refinement) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--contraction fp32]
-                    [--no-fast-mode] [--no-streamed] [--no-cpu-baseline]
+                    [--no-fast-mode] [--no-streamed] [--no-ceilings] [--no-cpu-baseline]
 
 The reported line is for --contraction (default fp32: float32 matrix instructions, the arithmetic the
 configurations name).  Unless --no-fast-mode is given, the same K steps are then timed once more
@@ -173,6 +173,7 @@ def main() -> int:
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="streamed fit: 0 = library default, -1 = in-kernel hand-off, > 0 = rows per chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceilings probe")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
                                                      "workload string then names the reduced N)")
@@ -330,6 +331,17 @@ def main() -> int:
                                "refine_iters": sstats[-1].refine_iters, "rmse": sstats[-1].rmse,
                                "workspace_bytes": sws.numel(),
                                "ordinary_fit_bytes": elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, True)}
+    if not args.no_ceilings:
+        # what this device sustains: register-resident matrix-instruction loops and a streaming copy
+        torch.cuda.empty_cache()
+        c = elm.probe_ceilings()
+        out["ceilings"] = c
+        r = out["roofline"]
+        if r.get("bound") == "mfma":
+            r["frac_of_measured"] = r["achieved"] / (c["mfma_f32_tflops"] if r["peak"] == PEAK_FP32_MFMA_TFLOPS
+                                                     else c["mfma_f16_tflops"])
+        if "fast_mode" in out:
+            out["fast_mode"]["roofline"]["frac_of_measured"] = out["fast_mode"]["roofline"]["achieved"] / c["mfma_f16_tflops"]
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
                                  "cfg5": 4096, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]

@@ -230,6 +230,17 @@ int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, i
 
 /* ---- diagnostics ---------------------------------------------------------------------------- */
 
+/* Measured ceilings of the current device, for quoting kernel rates against what the chip sustains as well
+ * as against its published peaks (the paper reports speed-ups only; this is measurement support, not
+ * part of the method): TFLOP/s of a register-resident loop of float32 32x32x2 and of fp16 32x32x16 matrix
+ * instructions (the two that step (2) is built on; 1,024 work-groups, four accumulators per wave), and
+ * GB/s (read + written) of a streaming copy of half the workspace onto the other half.  workspace: device,
+ * at least elm_rnn_probe_workspace_bytes() (2 GiB), contents destroyed.  Synchronises the stream. */
+size_t elm_rnn_probe_workspace_bytes(void);
+int elm_rnn_probe_ceilings(double* mfma_f32_tflops, double* mfma_f16_tflops, double* copy_gbs,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+
 const char* elm_rnn_strerror(int code);
 const char* elm_rnn_last_hip_error(void);
 

@@ -19,7 +19,7 @@ DECLARED_SYMBOLS = (
     "elm_rnn_solve", "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
     "elm_rnn_fit_streamed_workspace_bytes", "elm_rnn_fit_streamed",
     "elm_rnn_predict_workspace_bytes", "elm_rnn_predict", "elm_rnn_strerror",
-    "elm_rnn_last_hip_error",
+    "elm_rnn_last_hip_error", "elm_rnn_probe_workspace_bytes", "elm_rnn_probe_ceilings",
 )
 
 
@@ -101,6 +101,9 @@ def load_library():
     lib.elm_rnn_predict_workspace_bytes.argtypes = [i64, C.c_int]
     lib.elm_rnn_predict_workspace_bytes.restype = sz
     lib.elm_rnn_predict.argtypes = [vp, vp, i64, i64, i64, vp, vp, sz, vp]
+    lib.elm_rnn_probe_workspace_bytes.argtypes = []
+    lib.elm_rnn_probe_workspace_bytes.restype = sz
+    lib.elm_rnn_probe_ceilings.argtypes = [C.POINTER(C.c_double)] * 3 + [vp, sz, vp]
     lib.elm_rnn_strerror.argtypes = [C.c_int]
     lib.elm_rnn_strerror.restype = C.c_char_p
     lib.elm_rnn_last_hip_error.restype = C.c_char_p
@@ -357,6 +360,17 @@ def fit_streamed(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_ra
                                   C.byref(st), C.byref(out))
     _check(rc, allow_rank=allow_rank_deficient)
     return FitResult(Model(out.value, cell, Q, d, L, m), beta32, beta64, None, _stats(st, rc == ELM_ERANK))
+
+
+def probe_ceilings(stream=None) -> dict:
+    """elm_rnn_probe_ceilings: measured matrix-instruction and streaming-copy rates of the current device."""
+    import torch
+    lib = load_library()
+    ws = torch.empty(int(lib.elm_rnn_probe_workspace_bytes()), dtype=torch.uint8, device="cuda")
+    f32, f16, gbs = C.c_double(), C.c_double(), C.c_double()
+    _check(lib.elm_rnn_probe_ceilings(C.byref(f32), C.byref(f16), C.byref(gbs), ws.data_ptr(), ws.numel(),
+                                      _stream_ptr(stream)))
+    return {"mfma_f32_tflops": f32.value, "mfma_f16_tflops": f16.value, "hbm_copy_gbs": gbs.value}
 
 
 def predict(model: Model, X, workspace=None, stream=None):

@@ -127,3 +127,15 @@ def test_caller_stream_predict_and_set_beta(elm):
     Y2 = elm.predict(res.model, X).cpu().numpy()
     np.testing.assert_allclose(Y2, Href @ beta2, atol=2e-4)
     res.model.close()
+
+
+def test_ceilings_probe_reports_plausible_rates(elm):
+    """The measured-ceilings diagnostic: rates below the published peaks, above half of them."""
+    c = elm.probe_ceilings()
+    assert 80.0 < c["mfma_f32_tflops"] <= 157.3 * 1.02
+    assert 1000.0 < c["mfma_f16_tflops"] <= 2500.0 * 1.02
+    assert 2000.0 < c["hbm_copy_gbs"] <= 8000.0 * 1.02
+    lib = elm.load_library()
+    import ctypes as C
+    x = C.c_double()
+    assert lib.elm_rnn_probe_ceilings(C.byref(x), C.byref(x), C.byref(x), None, 0, None) == -2
