@@ -261,9 +261,13 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    stats = [step() for _ in range(args.steps)]
+    stats, marks = [], [t0]
+    for _ in range(args.steps):
+        stats.append(step())              # a fit synchronises its stream before it returns
+        marks.append(time.perf_counter())
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step_ms = [1e3 * (b - a) for a, b in zip(marks[:-1], marks[1:])]
 
     ms_per_step = 1e3 * dt / args.steps
     hidden_ms = float(np.mean([s.t_hidden_ms for s in stats]))     # HIP events on the launch stream
@@ -284,6 +288,8 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {cfg.cell} ELM-RNN fit, N={cfg.N}, Q={cfg.Q}, d={cfg.d}, "
                                f"L={cfg.L}, m={cfg.m}, materialised windows resident in HBM",
                    "hidden_ms": hidden_ms, "solve_ms": solve_ms,
+                   "host_ms": ms_per_step - hidden_ms - solve_ms,     # weights from the seed, packing, launches
+                   "ms_per_step_min": min(per_step_ms), "ms_per_step_median": float(np.median(per_step_ms)),
                    "hidden_samples_per_s": cfg.N / (hidden_ms * 1e-3),
                    "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
                    "contraction": args.contraction, "streamed": bool(args.streamed),
