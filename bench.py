@@ -350,7 +350,7 @@ def main() -> int:
             out["fast_mode"]["roofline"]["frac_of_measured"] = out["fast_mode"]["roofline"]["achieved"] / c["mfma_f16_tflops"]
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
-                                 "cfg5": 4096, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]
+                                 "cfg5": 8192, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]
         out["cpu_baseline"] = cpu_baseline(cfg, rows)
     print(json.dumps(out))
     return 0
