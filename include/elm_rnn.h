@@ -192,14 +192,16 @@ size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chu
  *   in-kernel hand-off  the stage-1 kernel runs a persistent grid, one work-group per level-0 R factor
  *                       of the TSQR; every finished tile [H(Q) | T] is rewritten in LDS as the next row
  *                       block and folded into that R factor before the work-group starts its next tile.
- *                       Exists for float32-contraction models of the dense cells whose layer is wide
- *                       enough that stage 1 runs one work-group per compute unit (LSTM L > 128,
- *                       Elman / GRU L > 256);
+ *                       Exists for float32-contraction models of the dense cells with more than 64
+ *                       units; where stage 1 runs one work-group per compute unit (LSTM L > 128,
+ *                       Elman / GRU L > 256) it costs nothing, where it runs two (32-row tiles) the
+ *                       folds take four times the Householder steps of the chunked form (4 % slower at
+ *                       L = 256), so the automatic mode uses it only for the former;
  *   chunked             H is produced one chunk of rows at a time into a buffer small enough to stay in
  *                       the memory-side cache and folded into the R factors by the TSQR's level 0 before
  *                       the next chunk overwrites it.  Any cell, any contraction.
- * chunk_rows = 0 picks the hand-off when it exists and N fills the level-0 grid (256 R factors), else
- * default chunks; chunk_rows > 0 asks for chunks of that many rows; chunk_rows = -1 asks for the
+ * chunk_rows = 0 picks the hand-off for the one-work-group-per-unit layers when N gives every work-group
+ * of the grid a tile, else default chunks; chunk_rows > 0 asks for chunks of that many rows; chunk_rows = -1 asks for the
  * hand-off and returns ELM_EUNSUPPORTED where it does not exist.
  * Same arguments and results as elm_rnn_fit (there is no H_out), and the same beta up to float32
  * rounding in the factorisation, except:

@@ -444,10 +444,28 @@ static int64_t streamed_chunk(int64_t N, int L, int64_t chunk_rows) {
     return chunk_rows < N ? chunk_rows : N;
 }
 
+// level-0 R factors the in-kernel hand-off may ask for: two work-groups per compute unit for the layers of at
+// most 256 units, one above; 256 compute units assumed when none is visible (sizes are asked for up front)
+static int streamed_fused_groups_bound(int L) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    const int64_t g = (int64_t)(L <= 256 ? 2 : 1) * cus;
+    return (int)(g > 1024 ? 1024 : g);
+}
+
+// solve-plan part of the streamed fit's workspace: room for either form's R factors
+static size_t streamed_plan_bytes(int64_t N, int L, int m) {
+    const size_t a = make_solve_plan(N, L, m).bytes;
+    const size_t b = make_solve_plan(N, L, m, streamed_fused_groups_bound(L)).bytes;
+    return a > b ? a : b;
+}
+
 size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows) {
-    const size_t s = elm_rnn_solve_workspace_bytes(N, L, m);
-    if (s == 0) return 0;
-    return s + (((size_t)streamed_chunk(N, L, chunk_rows) * L * sizeof(float) + 255) & ~(size_t)255);
+    if (elm_rnn_solve_workspace_bytes(N, L, m) == 0) return 0;
+    return streamed_plan_bytes(N, L, m) +
+           (((size_t)streamed_chunk(N, L, chunk_rows) * L * sizeof(float) + 255) & ~(size_t)255);
 }
 
 // max|R_jj| / min|R_jj| above which the automatic mode of the streamed fit refines beta: the normal-equation
@@ -468,13 +486,29 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
     if (workspace == nullptr || workspace_bytes < need) return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t chunk = streamed_chunk(N, L, chunk_rows);
-    const SolvePlan plan = make_solve_plan(N, L, m);
-    float* Hc = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.bytes);
-    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(workspace) + plan.off_small);
+    float* Hc = reinterpret_cast<float*>(static_cast<char*>(workspace) + streamed_plan_bytes(N, L, m));
 
     elm_rnn_model* mdl = nullptr;
     rc = elm_rnn_model_create(cell, Q, d, L, m, seed, init, &mdl);
     if (rc != ELM_OK) return rc;
+
+    // In-kernel hand-off (the tile goes from LDS into the fold) where stage 1 has such a variant: forced by
+    // chunk_rows == -1; chosen by default for the variants that run one work-group per compute unit when
+    // every work-group of the persistent grid gets a tile (the two-per-unit variants fold 32-row tiles,
+    // four times the Householder steps of the chunked level 0: measured 4 % slower at cfg4, so they are
+    // on request only).  The kernel brings its own number of level-0 R factors: the plan is made for it.
+    int per_cu = 1;
+    const int fused_groups = (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dWp != nullptr &&
+                              (mdl->cell == ELM_CELL_ELMAN || mdl->cell == ELM_CELL_LSTM || mdl->cell == ELM_CELL_GRU))
+                                 ? hidden_fused_groups(mdl->lay, N, m, &per_cu) : 0;
+    if (chunk_rows == -1 && (fused_groups == 0 || fused_groups > streamed_fused_groups_bound(L))) {
+        elm_rnn_free(mdl);
+        return ELM_EUNSUPPORTED;
+    }
+    const bool fuse = fused_groups > 0 && fused_groups <= streamed_fused_groups_bound(L) &&
+                      (chunk_rows == -1 || (chunk_rows == 0 && per_cu == 1 && fused_groups >= 256));
+    const SolvePlan plan = fuse ? make_solve_plan(N, L, m, fused_groups) : make_solve_plan(N, L, m);
+    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(workspace) + plan.off_small);
 
     // one event pair around every stage-1 launch: their sum is the stage-1 time, the rest of the
     // span is stage 2.  The pairs are summed (after a stream synchronisation) and reused every 64 chunks,
@@ -525,16 +559,6 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
         elm_rnn_free(mdl);
         return ELM_EHIP;
     };
-
-    // In-kernel hand-off (the tile goes from LDS into the fold) where stage 1 has such a variant: chosen
-    // by default when the level-0 grid of the plan fills the chip, forced by chunk_rows == -1.
-    const bool can_fuse = mdl->contraction == ELM_CONTRACT_FP32 && mdl->dWp != nullptr &&
-                          hidden_fused_available(mdl->lay, plan);
-    if (chunk_rows == -1 && !can_fuse) {
-        elm_rnn_free(mdl);
-        return ELM_EUNSUPPORTED;
-    }
-    const bool fuse = can_fuse && (chunk_rows == -1 || (chunk_rows == 0 && plan.groups[0] >= 256));
 
     hipError_t e = span.mark(stream);
     if (e == hipSuccess && fuse) {

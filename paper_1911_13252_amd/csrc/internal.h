@@ -76,7 +76,8 @@ struct SolvePlan {
     size_t off_small;      // beta64, gradient, scalars (doubles)
     size_t bytes;
 };
-SolvePlan make_solve_plan(int64_t N, int L, int m);
+// level0_groups > 0 fixes the number of level-0 R factors (at most 1024); 0 = chosen from N
+SolvePlan make_solve_plan(int64_t N, int L, int m, int level0_groups = 0);
 
 hipError_t launch_tsqr(const SolvePlan& plan, const float* H, const float* T, void* ws,
                        float** R_final, hipStream_t stream);
@@ -86,6 +87,11 @@ hipError_t launch_tsqr_level0(const SolvePlan& plan, const float* H, const float
 hipError_t launch_tsqr_combine(const SolvePlan& plan, void* ws, float** R_final, hipStream_t stream);
 // Stage 1 and level 0 of the TSQR in one kernel (H is never stored), for the layers whose stage-1 variant
 // runs one work-group per compute unit; the R factors land where launch_tsqr_level0 would put them.
+// hidden_fused_groups: the persistent grid the fused kernel wants for N rows (work-groups per compute unit of
+// its variant x compute units, at most one per tile), 0 where no fused variant exists; the plan passed to
+// launch_hidden_fused must have been made with that many level-0 groups.  *per_cu receives the variant's
+// work-groups per compute unit.
+int hidden_fused_groups(const PackedLayout& lay, int64_t N, int m, int* per_cu = nullptr);
 bool hidden_fused_available(const PackedLayout& lay, const SolvePlan& plan);
 hipError_t launch_hidden_fused(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
                                int64_t ldx_q, int64_t N, int Q, const float* T, const SolvePlan& plan,

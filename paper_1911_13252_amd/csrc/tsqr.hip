@@ -142,7 +142,7 @@ size_t fold_lds_bytes(int np, int br) { return fold::lds_floats(np, br) * sizeof
 
 }  // namespace
 
-SolvePlan make_solve_plan(int64_t N, int L, int m) {
+SolvePlan make_solve_plan(int64_t N, int L, int m, int level0_groups) {
     SolvePlan pl{};
     pl.N = N; pl.L = L; pl.m = m;
     pl.n = L + m;
@@ -153,6 +153,7 @@ SolvePlan make_solve_plan(int64_t N, int L, int m) {
     int64_t g0 = (nblocks + 3) / 4;
     if (g0 < 1) g0 = 1;
     if (g0 > 256) g0 = 256;
+    if (level0_groups > 0) g0 = level0_groups;      // the fused stage-1 kernel brings its own grid
     pl.levels = 0;
     pl.groups[pl.levels++] = (int)g0;
     while (pl.groups[pl.levels - 1] > 1) {

@@ -45,7 +45,9 @@ def test_host_only_entry_points(lib):
     # the streamed fit holds one chunk of H: whole 128-row blocks, at most N rows, 128 MiB by default
     assert elm.fit_streamed_workspace_bytes(4_000_000, 512, 2, 1000) - a == 1024 * 512 * 4
     assert elm.fit_streamed_workspace_bytes(4_000_000, 512, 2) - a == 65536 * 512 * 4
-    assert elm.fit_streamed_workspace_bytes(1000, 16, 1) == elm.fit_workspace_bytes(1000, 16, 1, True)
+    # (a narrow layer's in-kernel hand-off may bring up to two R factors per compute unit)
+    assert elm.fit_streamed_workspace_bytes(1000, 16, 1) >= elm.fit_workspace_bytes(1000, 16, 1, True)
+    assert elm.fit_streamed_workspace_bytes(1000, 16, 1) - elm.fit_workspace_bytes(1000, 16, 1, True) <= 1024 * 32 * 32 * 4 * 2
     assert elm.fit_streamed_workspace_bytes(1000, 513, 1, 0) == 0
 
 

@@ -95,6 +95,13 @@ FUSED_CASES = [  # data, cell, N, L: every stage-1 variant that has the in-kerne
     ("cfg4", "gru", 4500, 288),       # 64-row tiles
     ("cfg4", "gru", 4501, 320),       # 32-row tiles, three chunks
     ("cfg4", "gru", 4001, 448),       # 32-row tiles, four chunks
+    # layers of 65 .. 128 / 256 units: two work-groups per compute unit, 32-row folds
+    ("cfg3", "lstm", 5003, 96),
+    ("cfg3", "lstm", 3000, 128),
+    ("cfg5", "elman", 4100, 100),
+    ("cfg5", "elman", 4101, 200),
+    ("cfg4", "gru", 4502, 72),
+    ("cfg4", "gru", 4503, 256),
 ]
 
 
@@ -123,7 +130,7 @@ def test_fused_hand_off_meets_the_bars_of_the_ordinary_fit(elm, name, cell, n, L
 
 
 def test_fused_hand_off_is_refused_where_no_variant_exists(elm):
-    cfg, X, T, L = problem("cfg3", 3000, 100)
+    cfg, X, T, L = problem("cfg3", 3000, 64)       # at most 64 units: the waves split the rows of the tile
     Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
     with pytest.raises(elm.ElmRnnError) as err:
         elm.fit_streamed(cfg.cell, Xd, Td, L, cfg.seed, chunk_rows=-1, **cfg_kwargs(cfg))

@@ -101,7 +101,7 @@ def test_random_streamed_fit(elm, seed):
     L = int(rng.choice([rng.integers(4, 100), rng.integers(wide, 513)]))
     d, m, Q = int(rng.integers(3, 9)), int(rng.integers(1, 4)), int(rng.integers(2, 6))
     N = int(rng.integers(6 * L, 6 * L + 3000))
-    hand_off = L >= wide and rng.random() < 0.6
+    hand_off = L >= 65 and rng.random() < 0.6          # the in-kernel hand-off exists above 64 units
     chunk = -1 if hand_off else int(rng.choice([0, rng.integers(128, 2000)]))
     mode = "split16" if (not hand_off and rng.random() < 0.4) else "fp32"
     X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
