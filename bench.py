@@ -187,8 +187,9 @@ def main() -> int:
                          "counters in rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures ONE GPU only (the fit path is single-GPU; see DESIGN.md "
-              "for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures ONE GPU only (the fit path runs on a single GPU; rows are "
+              "independent, so it would shard by row ranges with one exchange of R factors); run with --gpus 1",
+              file=sys.stderr)
         return 2
 
     import torch
