@@ -379,6 +379,93 @@ __global__ __launch_bounds__(kThreads) void stream_rows_kernel(const float* __re
     }
 }
 
+// Same contract for narrow layers (L <= LG, m <= 4): a wave handles 64 / LG rows at a time, LG lanes
+// per row and one column per lane, so a 10-column matrix keeps 40 of 64 lanes busy instead of 10 and a
+// row's dot products need log2(LG) exchange steps instead of six.  Rows are contiguous in memory, so a
+// wave's loads stay coalesced.  Partial sums are added in a fixed order, as in stream_rows_kernel.
+template <int M, int MODE, int LG>
+__global__ __launch_bounds__(kThreads) void stream_narrow_kernel(const float* __restrict__ H,
+                                                                 const float* __restrict__ T, int64_t N, int L,
+                                                                 int m, const double* __restrict__ beta,
+                                                                 double* __restrict__ part,
+                                                                 float* __restrict__ Y) {
+    constexpr int RPW = 64 / LG;                   // rows per wave and pass
+    __shared__ double wsum[LG * M + 2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane % LG, slot = lane / LG;     // column of this lane, row slot inside the wave's pass
+    double bt[M], gacc[M];
+#pragma unroll
+    for (int c = 0; c < M; ++c) {
+        bt[c] = (j < L && c < m) ? beta[(size_t)j * m + c] : 0.0;
+        gacc[c] = 0.0;
+    }
+    double rss = 0.0, h2 = 0.0;
+    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * RPW + slot;
+    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
+    float hn = (first < N && j < L) ? H[first * L + j] : 0.0f;      // the next row is requested one pass ahead
+    for (int64_t base = first - slot; base < N; base += stride) {
+        const int64_t row = base + slot;
+        const float hv = hn;
+        const int64_t nxt = row + stride;
+        hn = (nxt < N && j < L) ? H[nxt * L + j] : 0.0f;
+        const double h = (double)hv;
+        double dot[M];
+#pragma unroll
+        for (int c = 0; c < M; ++c) dot[c] = h * bt[c];
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+#pragma unroll
+            for (int off = LG / 2; off > 0; off >>= 1) dot[c] += __shfl_xor(dot[c], off);
+        }
+        if (MODE == 0) {
+            h2 = fma(h, h, h2);
+            if (row < N) {
+#pragma unroll
+                for (int c = 0; c < M; ++c) {
+                    const double res = (c < m) ? (double)T[row * m + c] - dot[c] : 0.0;
+                    if (j == 0) rss = fma(res, res, rss);
+                    gacc[c] = fma(h, res, gacc[c]);
+                }
+            }
+        } else if (row < N && j < m) {
+            double v = dot[0];
+#pragma unroll
+            for (int c = 1; c < M; ++c) v = (j == c) ? dot[c] : v;
+            Y[row * m + j] = (float)v;
+        }
+    }
+    if (MODE == 0) {
+        // the row slots of a wave first (lanes LG, 2 LG, ... apart), then the 4 waves in order
+#pragma unroll
+        for (int off = LG; off < 64; off <<= 1) {
+#pragma unroll
+            for (int c = 0; c < M; ++c) gacc[c] += __shfl_xor(gacc[c], off);
+            rss += __shfl_xor(rss, off);
+        }
+        for (int off = 32; off > 0; off >>= 1) h2 += __shfl_xor(h2, off);
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w && lane < LG) {
+#pragma unroll
+                for (int c = 0; c < M; ++c) {
+                    const int idx = lane * M + c;
+                    wsum[idx] = (w == 0) ? gacc[c] : wsum[idx] + gacc[c];
+                }
+                if (lane == 0) {
+                    wsum[LG * M] = (w == 0) ? rss : wsum[LG * M] + rss;
+                    wsum[LG * M + 1] = (w == 0) ? h2 : wsum[LG * M + 1] + h2;
+                }
+            }
+            __syncthreads();
+        }
+        double* mypart = part + (size_t)blockIdx.x * ((size_t)L * m + 2);
+        for (int idx = tid; idx < L * m; idx += kThreads) {
+            const int jx = idx / m, c = idx - jx * m;
+            mypart[idx] = wsum[jx * M + c];
+        }
+        if (tid < 2) mypart[(size_t)L * m + tid] = wsum[LG * M + tid];
+    }
+}
+
 // Sum the per-work-group partials in a fixed order.  Thread (o, q) of a work-group adds the
 // partials w = q, q+8, ... of output o; the 8 sub-sums are then added in order.
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part,
@@ -442,6 +529,23 @@ hipError_t launch_stream(const float* H, const float* T, int64_t N, int L, int m
     const int grid = stream_grid(N);
     int M = 1;
     while (M < m) M *= 2;
+    if (M <= 4 && L <= 32) {        // narrow layers: several rows per wave
+#define ELM_NARROW_LAUNCH(MM, GG)                                                                          \
+    hipLaunchKernelGGL((stream_narrow_kernel<MM, MODE, GG>), dim3(grid), dim3(kThreads), 0, stream, H, T, N, L, \
+                       m, beta, part, Y)
+#define ELM_NARROW_CASE(MM)                                 \
+    if (L <= 8) ELM_NARROW_LAUNCH(MM, 8);                   \
+    else if (L <= 16) ELM_NARROW_LAUNCH(MM, 16);            \
+    else ELM_NARROW_LAUNCH(MM, 32)
+        switch (M) {
+            case 1: ELM_NARROW_CASE(1); break;
+            case 2: ELM_NARROW_CASE(2); break;
+            default: ELM_NARROW_CASE(4); break;
+        }
+#undef ELM_NARROW_CASE
+#undef ELM_NARROW_LAUNCH
+        return hipGetLastError();
+    }
     if (M <= 4 && L <= 512) {       // register-resident variant, columns per lane sized to L
 #define ELM_ROWS_LAUNCH(MM, EE)                                                                        \
     hipLaunchKernelGGL((stream_rows_kernel<MM, MODE, EE>), dim3(grid), dim3(kThreads), 0, stream, H, T, N, L, \
