@@ -476,8 +476,19 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
     const int nout = L * m + 2;
     const int o = blockIdx.x * 32 + ol;
     double s = 0.0;
-    if (o < nout)
-        for (int w = q; w < nparts; w += 8) s += part[(size_t)w * nout + o];
+    if (o < nout) {
+        // partials w = q, q + 8, ... in that order; eight loads are in flight at a time
+        for (int w0 = q; w0 < nparts; w0 += 64) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int w = w0 + 8 * u;
+                v[u] = (w < nparts) ? part[(size_t)w * nout + o] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+    }
     sub[q][ol] = s;
     __syncthreads();
     if (q == 0 && o < nout) {

@@ -44,8 +44,8 @@ struct FoldArgs {
 
 // BR = rows per folded block (64 or 128).  Taller blocks halve the number of sequential
 // Householder steps per input row; they are used whenever the block fits in LDS.
-template <int BR>
-__global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
+template <int BR, bool ONE_PANEL = false>
+__global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(const FoldArgs a) {
     extern __shared__ __align__(16) float lds[];
     const int np = a.np, ldb = a.ldb;
     float* Bs = lds;                           // [BR][ldb], then the scratch areas of fold_block
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void tsqr_fold_kernel(const FoldArgs a) {
         }
         __syncthreads();
 
-        fold_block<BR>(R, lds, np, ldb, p0);
+        fold_block<BR, ONE_PANEL>(R, lds, np, ldb, p0);
     }
 }
 
@@ -152,7 +152,10 @@ SolvePlan make_solve_plan(int64_t N, int L, int m, int level0_groups) {
     const int64_t nblocks = (N + pl.block_rows - 1) / pl.block_rows;
     int64_t g0 = (nblocks + 3) / 4;
     if (g0 < 1) g0 = 1;
-    if (g0 > 256) g0 = 256;
+    // one work-group per compute unit; three where the width is a single panel (np == 32: that kernel
+    // needs few registers and little LDS, and its Householder chains then overlap)
+    const int64_t cap = (pl.np == 32) ? 768 : 256;
+    if (g0 > cap) g0 = cap;
     if (level0_groups > 0) g0 = level0_groups;      // the fused stage-1 kernel brings its own grid
     pl.levels = 0;
     pl.groups[pl.levels++] = (int)g0;
@@ -189,7 +192,8 @@ hipError_t fold_launch_config(const SolvePlan& pl, FoldLaunch* fl) {
     const bool tall = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max && pl.block_rows == 128;
     fl->br = tall ? 128 : 64;
     fl->lds = fold_lds_bytes(pl.np, fl->br);
-    fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+    if (pl.np == 32) fl->kern = tall ? tsqr_fold_kernel<128, true> : tsqr_fold_kernel<64, true>;
+    else fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
 }

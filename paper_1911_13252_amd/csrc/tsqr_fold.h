@@ -41,7 +41,9 @@ __host__ __device__ inline size_t lds_floats(int np, int br) {
 // R: this work-group's np x np upper-triangular factor (global memory); lds: the block at lds[0 .. BR*ldb)
 // followed by the scratch areas; p0: first panel that can be non-zero in the block (columns left of it
 // are zero).  All 256 threads call it; it ends with a barrier.
-template <int BR>
+// ONE_PANEL: np == 32, the whole width is one panel: no T factor, no trailing update, and far fewer
+// registers, so that several work-groups share a compute unit.
+template <int BR, bool ONE_PANEL = false>
 __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, int np, int ldb, int p0) {
     constexpr int RPT = BR / 8;      // rows of a panel column held by one lane
     constexpr int MT = BR / 32;      // 32-row accumulator tiles per block
@@ -112,20 +114,22 @@ __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, in
             const float cf = (j == k) ? f : -(f * w);
 #pragma unroll
             for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, (j == k) ? 0.0f : pv[i]);
-            if (g == 0) {
+            if (!ONE_PANEL && g == 0) {
                 if (j == k) taus[k] = tau;
                 if (j < k) Gs[j * kGs + k] = f * sj;      // v_j . v_k for the finished reflector j
             }
         }
+        if (!ONE_PANEL) {                 // the trailing update reads the reflectors from the block
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) Bs[(RPT * g + i) * ldb + kp + j] = pv[i];
+            for (int i = 0; i < RPT; ++i) Bs[(RPT * g + i) * ldb + kp + j] = pv[i];
+        }
         if (g == 0) {
 #pragma unroll
             for (int k = 0; k < 32; ++k)
                 if (k <= j) R[(size_t)(kp + k) * np + kp + j] = rdv[k];
         }
         __syncthreads();
-        if (p + 1 == NP) break;       // last panel: nothing to the right
+        if (ONE_PANEL || p + 1 == NP) break;       // last panel: nothing to the right
 
         // next panel's diagonal block of R: in flight during the T factor and trailing update
 #pragma unroll
