@@ -389,10 +389,11 @@ __global__ __launch_bounds__(kThreads) void stream_narrow_kernel(const float* __
                                                                  int m, const double* __restrict__ beta,
                                                                  double* __restrict__ part,
                                                                  float* __restrict__ Y) {
-    constexpr int RPW = 64 / LG;                   // rows per wave and pass
+    constexpr int RPW = 64 / LG;                   // rows a wave covers with one load
+    constexpr int UNR = 4;                         // independent loads / reductions in flight per lane
     __shared__ double wsum[LG * M + 2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int j = lane % LG, slot = lane / LG;     // column of this lane, row slot inside the wave's pass
+    const int j = lane % LG, slot = lane / LG;     // column of this lane, row slot inside a group of RPW rows
     double bt[M], gacc[M];
 #pragma unroll
     for (int c = 0; c < M; ++c) {
@@ -400,38 +401,54 @@ __global__ __launch_bounds__(kThreads) void stream_narrow_kernel(const float* __
         gacc[c] = 0.0;
     }
     double rss = 0.0, h2 = 0.0;
-    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * RPW + slot;
-    const int64_t stride = (int64_t)gridDim.x * 4 * RPW;
-    float hn = (first < N && j < L) ? H[first * L + j] : 0.0f;      // the next row is requested one pass ahead
-    for (int64_t base = first - slot; base < N; base += stride) {
-        const int64_t row = base + slot;
-        const float hv = hn;
-        const int64_t nxt = row + stride;
-        hn = (nxt < N && j < L) ? H[nxt * L + j] : 0.0f;
-        const double h = (double)hv;
-        double dot[M];
+    // a wave takes UNR * RPW consecutive rows per pass: lane (slot, j) the rows base + u * RPW + slot
+    const int64_t first = ((int64_t)blockIdx.x * 4 + wave) * (UNR * RPW);
+    const int64_t stride = (int64_t)gridDim.x * 4 * (UNR * RPW);
+    float hn[UNR];                                 // the next pass is requested one pass ahead
 #pragma unroll
-        for (int c = 0; c < M; ++c) dot[c] = h * bt[c];
+    for (int u = 0; u < UNR; ++u) {
+        const int64_t row = first + u * RPW + slot;
+        hn[u] = (row < N && j < L) ? H[row * L + j] : 0.0f;
+    }
+    for (int64_t base = first; base < N; base += stride) {
+        float hv[UNR];
 #pragma unroll
-        for (int c = 0; c < M; ++c) {
-#pragma unroll
-            for (int off = LG / 2; off > 0; off >>= 1) dot[c] += __shfl_xor(dot[c], off);
+        for (int u = 0; u < UNR; ++u) {
+            hv[u] = hn[u];
+            const int64_t nxt = base + stride + u * RPW + slot;
+            hn[u] = (nxt < N && j < L) ? H[nxt * L + j] : 0.0f;
         }
-        if (MODE == 0) {
-            h2 = fma(h, h, h2);
-            if (row < N) {
+        double dot[UNR][M];
 #pragma unroll
-                for (int c = 0; c < M; ++c) {
-                    const double res = (c < m) ? (double)T[row * m + c] - dot[c] : 0.0;
-                    if (j == 0) rss = fma(res, res, rss);
-                    gacc[c] = fma(h, res, gacc[c]);
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int c = 0; c < M; ++c) dot[u][c] = (double)hv[u] * bt[c];
+#pragma unroll
+        for (int off = LG / 2; off > 0; off >>= 1)
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int c = 0; c < M; ++c) dot[u][c] += __shfl_xor(dot[u][c], off);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t row = base + u * RPW + slot;
+            const double h = (double)hv[u];
+            if (MODE == 0) {
+                h2 = fma(h, h, h2);
+                if (row < N) {
+#pragma unroll
+                    for (int c = 0; c < M; ++c) {
+                        const double res = (c < m) ? (double)T[row * m + c] - dot[u][c] : 0.0;
+                        if (j == 0) rss = fma(res, res, rss);
+                        gacc[c] = fma(h, res, gacc[c]);
+                    }
                 }
-            }
-        } else if (row < N && j < m) {
-            double v = dot[0];
+            } else if (row < N && j < m) {
+                double v = dot[u][0];
 #pragma unroll
-            for (int c = 1; c < M; ++c) v = (j == c) ? dot[c] : v;
-            Y[row * m + j] = (float)v;
+                for (int c = 1; c < M; ++c) v = (j == c) ? dot[u][c] : v;
+                Y[row * m + j] = (float)v;
+            }
         }
     }
     if (MODE == 0) {

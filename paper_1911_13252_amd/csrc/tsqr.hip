@@ -182,7 +182,7 @@ struct FoldLaunch {
     size_t lds;
 };
 
-hipError_t fold_launch_config(const SolvePlan& pl, FoldLaunch* fl) {
+hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl) {
     int dev = 0, lds_max = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -192,8 +192,16 @@ hipError_t fold_launch_config(const SolvePlan& pl, FoldLaunch* fl) {
     const bool tall = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max && pl.block_rows == 128;
     fl->br = tall ? 128 : 64;
     fl->lds = fold_lds_bytes(pl.np, fl->br);
-    if (pl.np == 32) fl->kern = tall ? tsqr_fold_kernel<128, true> : tsqr_fold_kernel<64, true>;
-    else fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+    if (pl.np == 32 && combine) {
+        // a 32 x 32 triangular input is one 32-row block: the shortest Householder steps
+        fl->br = 32;
+        fl->lds = fold_lds_bytes(pl.np, 32);
+        fl->kern = tsqr_fold_kernel<32, true>;
+    } else if (pl.np == 32) {
+        fl->kern = tall ? tsqr_fold_kernel<128, true> : tsqr_fold_kernel<64, true>;
+    } else {
+        fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+    }
     return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
 }
@@ -206,7 +214,7 @@ hipError_t fold_launch_config(const SolvePlan& pl, FoldLaunch* fl) {
 hipError_t launch_tsqr_level0(const SolvePlan& pl, const float* H, const float* T, int64_t rows, void* ws,
                               int keep, hipStream_t stream) {
     FoldLaunch fl{};
-    hipError_t e = fold_launch_config(pl, &fl);
+    hipError_t e = fold_launch_config(pl, false, &fl);
     if (e != hipSuccess) return e;
     FoldArgs a{};
     a.np = pl.np;
@@ -224,7 +232,7 @@ hipError_t launch_tsqr_level0(const SolvePlan& pl, const float* H, const float* 
 // The combine levels: merge the level-0 R factors pairwise until one is left.
 hipError_t launch_tsqr_combine(const SolvePlan& pl, void* ws, float** R_final, hipStream_t stream) {
     FoldLaunch fl{};
-    hipError_t e = fold_launch_config(pl, &fl);
+    hipError_t e = fold_launch_config(pl, true, &fl);
     if (e != hipSuccess) return e;
     char* base = static_cast<char*>(ws);
     *R_final = reinterpret_cast<float*>(base + pl.off_R[0]);
