@@ -15,6 +15,7 @@ struct elm_rnn_model {
     elm::PackedLayout lay;
     std::vector<float> W, U, b;   // host copies, float32
     float* dWp = nullptr;         // packed [W; b; U] on the device (dense cells; rotations for the multi-lag cell)
+    float* dTiny = nullptr;       // dense cells of at most kTinyMaxL units: [b; W; U] rows padded for the vector-ALU kernel
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
@@ -142,6 +143,12 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         pack_weights(mdl->lay, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
     }
     hipError_t e = hipMalloc(dst, packed.size() * sizeof(float));
+    if (e == hipSuccess && tiny_padded_units(cell, L) > 0) {
+        std::vector<float> tiny(tiny_packed_floats(cell, d, L));
+        pack_weights_tiny(cell, d, L, mdl->W.data(), mdl->U.data(), mdl->b.data(), tiny.data());
+        e = hipMalloc(&mdl->dTiny, tiny.size() * sizeof(float));
+        if (e == hipSuccess) e = hipMemcpy(mdl->dTiny, tiny.data(), tiny.size() * sizeof(float), hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
@@ -179,6 +186,8 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
         return launch_hidden_diag(Wt, alpha, bias, mdl->Q, X, ldx_n, ldx_q, N, Q_run, mdl->d, mdl->L, H,
                                   stream);
     }
+    if (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dTiny != nullptr)
+        return launch_hidden_tiny(mdl->cell, mdl->d, mdl->L, mdl->dTiny, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     if (mdl->contraction == ELM_CONTRACT_SPLIT16 && mdl->dWs != nullptr)
         return launch_hidden_split(mdl->slay, mdl->dWs, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     return launch_hidden(mdl->lay, mdl->dWp, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
@@ -337,6 +346,7 @@ int elm_rnn_set_beta(elm_rnn_model* model, const double* beta64) {
 void elm_rnn_free(elm_rnn_model* model) {
     if (model == nullptr) return;
     if (model->dWp) (void)hipFree(model->dWp);
+    if (model->dTiny) (void)hipFree(model->dTiny);
     if (model->dDiag) (void)hipFree(model->dDiag);
     if (model->dWs) (void)hipFree(model->dWs);
     if (model->dBeta) (void)hipFree(model->dBeta);

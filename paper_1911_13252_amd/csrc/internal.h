@@ -35,6 +35,15 @@ hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* 
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
                          float* H, float* C, hipStream_t stream);
 
+// ---- layers of a few units on the vector ALU (a lane per sample); float32 contraction only
+constexpr int kTinyMaxL = 12;
+int tiny_padded_units(int cell, int L);                 // 0: no such kernel for this cell / width
+size_t tiny_packed_floats(int cell, int d, int L);
+void pack_weights_tiny(int cell, int d, int L, const float* W, const float* U, const float* b, float* out);
+hipError_t launch_hidden_tiny(int cell, int d, int L, const float* Wp, const float* X, int64_t ldx_n, int64_t ldx_q,
+                              int64_t N, int Q_run, const float* h0, const float* c0, float* H, float* C,
+                              hipStream_t stream);
+
 // Spectral radius of a row-major n x n float64 host matrix, computed on the current device.
 hipError_t spectral_radius_device(const double* A, int n, double* rho_out);
 
