@@ -121,6 +121,16 @@ def run_sweep(elm, torch, steps: int) -> dict:
                 r = timed_fit(dataclasses.replace(b, L=L), X, T, mode)
                 r["study"] = "hidden-size sweep"
                 rows.append(r)
+    # the paper's fully connected cell over the same hidden sizes at Q = 50: up to 20 units the history of a
+    # window stays in LDS, beyond that every step is a launch over a device-resident history
+    b = synthdata.get_config("paper_fc_q50")
+    X, T = windows(b)
+    for L in (5, 10, 20, 50, 100):
+        c = dataclasses.replace(b, L=L)
+        r = timed_fit(c, X, T, "fp32")
+        r["study"] = "hidden-size sweep"
+        r["stage1_tflops"] = stage1_flops(c) / (r["hidden_ms"] * 1e-3) / 1e12
+        rows.append(r)
     for cell in ("elman", "lstm", "gru"):
         b = dataclasses.replace(base[cell], N=4500, Q=3197, L=50)
         X, T = windows(b)
@@ -241,6 +251,8 @@ def main() -> int:
                  "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                  "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                  "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"}
+            if cfg.cell == "fc_multilag" and (cfg.Q - 1) * cfg.L + cfg.d + 1 > 1272:
+                r["kernel"] = "fc_step_kernel (stage 1, one launch per step, fp32 MFMA 32x32x2)"
             return r
         # three fp16 matrix instructions per algorithmic product (hi*hi, hi*lo, lo*hi): the
         # algorithmic rate can reach at most a third of the fp16 peak
@@ -351,7 +363,8 @@ def main() -> int:
             out["fast_mode"]["roofline"]["frac_of_measured"] = out["fast_mode"]["roofline"]["achieved"] / c["mfma_f16_tflops"]
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
-                                 "cfg5": 8192, "paper_elman": 20_000, "paper_fc": 20_000}[cfg.name]
+                                 "cfg5": 8192, "paper_elman": 20_000, "paper_fc": 20_000,
+                                 "paper_fc_q50": 20_000}[cfg.name]
         out["cpu_baseline"] = cpu_baseline(cfg, rows)
     print(json.dumps(out))
     return 0

@@ -58,8 +58,15 @@ extern "C" {
                                 by every neuron's output of all earlier steps of the window:
                                 h(t) = tanh(x(t) W + b + sum_{k=1}^{t-1} h(t-k) A_k);
                                 its recurrent array "U" is A, Q x L x L (A[k-1][m][j]: neuron m, k steps
-                                ago, into neuron j; the last block is never used); needs
-                                max(Q-1,1)*L + d + 1 <= 1272; no initial state, Q_run <= Q          */
+                                ago, into neuron j; the last block is never used); no initial state,
+                                Q_run <= Q.  While the history of a window is short (max(Q-1,1)*L + d + 1
+                                <= 1272, and <= 640 for L <= 64) it stays on chip for all steps; beyond
+                                that every step is a launch of its own over a device buffer of past
+                                states that the model owns (allocated at creation, below 2 GiB: room for
+                                up to 65,536 rows, more rows are taken in passes).  Calls that build H
+                                from one such model must not overlap in time (they share that buffer).
+                                ELM_EUNSUPPORTED if a window's history exceeds 8 MiB or the packed lag
+                                matrices 4 GiB                                                       */
 
 /* How the dense cells carry the recurrent contraction h_{t-1} U of each step (the input part x_t W + b
  * and all point-wise work are float32-exact in both):

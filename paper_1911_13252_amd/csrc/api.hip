@@ -17,6 +17,9 @@ struct elm_rnn_model {
     float* dWp = nullptr;         // packed [W; b; U] on the device (dense cells; rotations for the multi-lag cell)
     float* dTiny = nullptr;       // dense cells of at most kTinyMaxL units: [b; W; U] rows padded for the vector-ALU kernel
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
+    elm::FcStepLayout fcs{};      // ELM_CELL_FC_MULTILAG beyond what LDS holds: one launch per step with
+    float* dFcW = nullptr;        //   the packed stack [A_{Q-1}; ...; A_1; W; b] and
+    float* dFcHist = nullptr;     //   the past states of a chunk of rows (scratch of every hidden-matrix call)
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
     void* dWs = nullptr;
@@ -98,6 +101,15 @@ double spectral_radius(const std::vector<double>& A, int n) {
 // history slots of the fully connected multi-lag cell: lags 1 .. Q-1 can occur inside a window
 int fc_ring(int Q) { return Q > 1 ? Q - 1 : 1; }
 
+// The multi-lag cell keeps the operand row [x | 1 | Q-1 slots of L] in LDS for all steps while a
+// 32-sample tile of it fits; layers of at most two column blocks then leave waves idle (the tile cannot
+// grow to the rows they would take), and past 640 columns the launch-per-step form is the faster one
+// (measured at Q = 50, N = 700,000: L = 20 19.7 ms against 37.2 ms; L = 10 13.8 ms against 10.4 ms).
+bool fc_in_lds(int Q, int d, int L) {
+    const int64_t K = (int64_t)fc_ring(Q) * L + d + 1;
+    return K <= kFcMaxK && (L > 64 || K <= 640);
+}
+
 int check_dims(int cell, int Q, int d, int L, int m) {
     if (cell != ELM_CELL_ELMAN && cell != ELM_CELL_LSTM && cell != ELM_CELL_GRU &&
         cell != ELM_CELL_ELMAN_DIAG && cell != ELM_CELL_FC_MULTILAG)
@@ -105,7 +117,8 @@ int check_dims(int cell, int Q, int d, int L, int m) {
     if (Q < 1 || d < 1 || L < 1 || m < 1) return ELM_EINVAL;
     if (L > 512 || d > 64 || m > 16) return ELM_EUNSUPPORTED;
     if (cell == ELM_CELL_ELMAN_DIAG && Q > kDiagMaxQ) return ELM_EUNSUPPORTED;
-    if (cell == ELM_CELL_FC_MULTILAG && (int64_t)fc_ring(Q) * L + d + 1 > kFcMaxK) return ELM_EUNSUPPORTED;
+    if (cell == ELM_CELL_FC_MULTILAG && !fc_in_lds(Q, d, L) && !fc_step_layout(Q, d, L, nullptr))
+        return ELM_EUNSUPPORTED;
     return ELM_OK;
 }
 
@@ -133,6 +146,15 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         std::copy(mdl->U.begin(), mdl->U.end(), packed.begin() + (size_t)L * d);
         std::copy(mdl->b.begin(), mdl->b.end(), packed.begin() + (size_t)L * d + (size_t)L * Q);
         dst = &mdl->dDiag;
+    } else if (cell == ELM_CELL_FC_MULTILAG && !fc_in_lds(Q, d, L)) {
+        mdl->lay = PackedLayout{};
+        if (!fc_step_layout(Q, d, L, &mdl->fcs)) {
+            delete mdl;
+            return ELM_EUNSUPPORTED;
+        }
+        packed.resize(mdl->fcs.floats);
+        pack_weights_fc_steps(mdl->fcs, mdl->W.data(), mdl->U.data(), mdl->b.data(), packed.data());
+        dst = &mdl->dFcW;
     } else if (cell == ELM_CELL_FC_MULTILAG) {
         mdl->lay = packed_layout(cell, d, L, fc_ring(Q));
         packed.resize(mdl->lay.floats);
@@ -149,6 +171,7 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         e = hipMalloc(&mdl->dTiny, tiny.size() * sizeof(float));
         if (e == hipSuccess) e = hipMemcpy(mdl->dTiny, tiny.data(), tiny.size() * sizeof(float), hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcHist, mdl->fcs.hist_floats * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
@@ -186,6 +209,8 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
         return launch_hidden_diag(Wt, alpha, bias, mdl->Q, X, ldx_n, ldx_q, N, Q_run, mdl->d, mdl->L, H,
                                   stream);
     }
+    if (mdl->dFcW != nullptr)
+        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcHist, X, ldx_n, ldx_q, N, Q_run, H, stream);
     if (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dTiny != nullptr)
         return launch_hidden_tiny(mdl->cell, mdl->d, mdl->L, mdl->dTiny, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     if (mdl->contraction == ELM_CONTRACT_SPLIT16 && mdl->dWs != nullptr)
@@ -348,6 +373,8 @@ void elm_rnn_free(elm_rnn_model* model) {
     if (model->dWp) (void)hipFree(model->dWp);
     if (model->dTiny) (void)hipFree(model->dTiny);
     if (model->dDiag) (void)hipFree(model->dDiag);
+    if (model->dFcW) (void)hipFree(model->dFcW);
+    if (model->dFcHist) (void)hipFree(model->dFcHist);
     if (model->dWs) (void)hipFree(model->dWs);
     if (model->dBeta) (void)hipFree(model->dBeta);
     delete model;

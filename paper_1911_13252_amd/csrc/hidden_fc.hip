@@ -1,0 +1,287 @@
+// Stage 1 for the paper's fully connected multi-lag cell (section "Fully Connected RNN", Eq. hij_fc)
+// when the history of a window does not fit LDS: one launch per step over all rows.
+//
+//   h(t) = tanh( [h(1) | h(2) | ... | h(t-1) | x_t | 1] . [A_{t-1}; A_{t-2}; ...; A_1; W; b] )
+//
+// The states of a chunk of rows are kept in time order in a device buffer (row stride (Q-1)*Lk, a slot
+// of Lk = L rounded up to 8 columns per step), so the operand of step t is a prefix of the row followed
+// by the input, and its weights are a suffix of one stack [A_{Q-1}; ...; A_1; W; b]: nothing is
+// shifted or rotated, every step is a plain (rows x K_t) . (K_t x L) contraction with K_t growing by
+// Lk per step.  A work-group streams its rows of the operand through LDS in chunks of 64 columns
+// (double-buffered, global loads one chunk ahead in registers); every wave owns a 32-column block of
+// the output and reads its weight fragments straight from L2 in a pre-packed order, eight k-groups
+// ahead.  The history is read once per step: (t-1)*Lk*4 bytes per row against 2*(t-1)*Lk*L flops.
+//
+// The paper's kernel keeps the history of one (sample, neuron) pair per thread (its H_loc) and so
+// re-reads every other neuron's past outputs from global memory per thread; here a step is one
+// matrix-core contraction shared by the tile.
+
+#include "hidden_kernel.h"
+
+namespace elm {
+namespace {
+
+using namespace hk;
+
+constexpr int kBK = 64;            // operand columns per LDS chunk (8 k-groups)
+constexpr int kRS = kBK + 4;       // LDS row stride in floats (conflict-free 16-byte reads)
+constexpr int kPF = 8;             // weight k-groups in flight per wave = one chunk
+
+struct FcStepArgs {
+    const float* hist;     // [rows][ldh]: h(1) .. h(t-1) of this chunk of rows
+    int64_t ldh;
+    unsigned hist_bytes;   // rows * ldh * 4 (below 2^31)
+    const float* X;        // x_t of the chunk's first row
+    int64_t ldx_n;
+    const float* Wp;       // packed weight stack
+    unsigned wp_bytes;
+    unsigned kg0;          // first k-group of this step's weights inside a column block
+    unsigned jb_stride;    // bytes between the column blocks of the packed stack
+    int nchunks;           // chunks of kBK operand columns
+    int Kh;                // history columns of this step, (t-1)*Lk
+    int d, L, nJB;
+    int rows;
+    float* out;            // history slot t-1 (ldo = ldh) or H (ldo = L)
+    int64_t ldo;
+    int ncols;             // columns stored per row; those at or beyond L are zeros
+};
+
+// MS 32-row blocks per wave, CW column blocks per work-group (the other 4/CW waves take further rows)
+template <int MS, int CW>
+__global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p) {
+    constexpr int WR = 4 / CW, S = 32 * MS * WR, NLD = S / 16;
+    extern __shared__ float lds[];             // [2][S][kRS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wcol = wave % CW, rbase = (wave / CW) * 32 * MS;
+    const int jb = (int)blockIdx.y * CW + wcol;
+    const bool active = jb < p.nJB;            // the last group of column blocks may be short
+    const int64_t row0 = (int64_t)blockIdx.x * S;
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
+    const unsigned wbase = (unsigned)(active ? jb : 0) * p.jb_stride + p.kg0 * 1024u;
+    const unsigned voff = (unsigned)lane * 16u;
+
+    // this thread's NLD 16-byte pieces of a chunk: row (tid>>4) + 16*q, columns 4*(tid&15) .. +3
+    const int lr = tid >> 4, lk = (tid & 15) * 4;
+    const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.hist), 0, (int)p.hist_bytes, 0x00020000);
+    unsigned hoff[NLD];                        // byte offset of the piece in chunk 0; rows past the end: out of range
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int64_t row = row0 + lr + 16 * q;
+        hoff[q] = row < p.rows ? (unsigned)((row * p.ldh + lk) * 4) : 0xFFFFFFF0u;
+    }
+    floatx4 stage[NLD];
+    // a chunk that lies inside the history: range-checked loads, rows past the end read as zero
+    auto load_history = [&](int c) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const unsigned off = hoff[q] == 0xFFFFFFF0u ? hoff[q] : hoff[q] + (unsigned)c * (kBK * 4u);
+            stage[q] = buffer_load_x4(hrs, off, 0);
+        }
+    };
+    // a chunk that holds the end of the history, x_t, the constant 1 and the zero padding
+    auto load_edge = [&](int c) {
+        const int k = c * kBK + lk;
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int64_t row = row0 + lr + 16 * q;
+            floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (row < p.rows) {
+                if (k < p.Kh) {            // Kh and k are multiples of 4: a piece never straddles the edge
+                    v = *reinterpret_cast<const floatx4*>(p.hist + row * p.ldh + k);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int kk = k + e - p.Kh;
+                        v[e] = kk < p.d ? p.X[row * p.ldx_n + kk] : (kk == p.d ? 1.0f : 0.0f);
+                    }
+                }
+            }
+            stage[q] = v;
+        }
+    };
+    auto store_chunk = [&](float* buf) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q)
+            *reinterpret_cast<floatx4*>(buf + (lr + 16 * q) * kRS + lk) = stage[q];
+    };
+
+    floatx16 acc[MS];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[ms][i] = 0.0f;
+
+    floatx4 bq[kPF];
+#pragma unroll
+    for (int u = 0; u < kPF; ++u) bq[u] = buffer_load_x4(wrs, voff, wbase + (unsigned)u * 1024u);
+
+    // the kPF k-groups of chunk c; every weight slot is refilled with the group one chunk ahead (the
+    // stack ends in zero groups, so the look-ahead past the last chunk needs no test)
+    auto compute = [&](int c) {
+        const float* ap = lds + (c & 1) * S * kRS + (rbase + (lane & 31)) * kRS + (lane >> 5) * 4;
+        const unsigned wnext = wbase + (unsigned)(c * kPF + kPF) * 1024u;
+        floatx4 a[MS];
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) a[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * kRS);
+#pragma unroll
+        for (int u = 0; u < kPF; ++u) {
+            floatx4 an[MS];                         // operand fragment of the next group, read under the MFMAs
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+                an[ms] = *reinterpret_cast<const floatx4*>(ap + ms * 32 * kRS + (u + 1 < kPF ? u + 1 : u) * 8);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    acc[ms] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ms][e], bq[u][e], acc[ms], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);      // the refill is issued here, not at the end of the chunk
+            bq[u] = buffer_load_x4(wrs, voff, wnext + (unsigned)u * 1024u);
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) a[ms] = an[ms];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int nfull = p.Kh / kBK;              // chunks that lie inside the history
+    if (nfull > 0) load_history(0); else load_edge(0);
+    store_chunk(lds);
+    __syncthreads();
+    int c = 0;
+    for (; c + 1 < nfull; ++c) {               // chunk c + 1 is fetched while chunk c is contracted
+        load_history(c + 1);
+        __builtin_amdgcn_sched_barrier(0);          // the operand loads have the whole chunk to arrive
+        compute(c);
+        store_chunk(lds + ((c + 1) & 1) * S * kRS);
+        __syncthreads();
+    }
+    for (; c < p.nchunks; ++c) {
+        const bool more = c + 1 < p.nchunks;
+        if (more) load_edge(c + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(c);
+        if (more) store_chunk(lds + ((c + 1) & 1) * S * kRS);
+        __syncthreads();
+    }
+
+    if (!active) return;
+    const int col = jb * 32 + (lane & 31);
+    if (col >= p.ncols) return;
+    const bool real = col < p.L;
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t row = row0 + rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            if (row < p.rows) p.out[row * p.ldo + col] = real ? tanh_f(acc[ms][i]) : 0.0f;
+        }
+}
+
+template <int MS, int CW>
+hipError_t launch_step(const FcStepArgs& a, int ycount, hipStream_t stream) {
+    constexpr int S = 32 * MS * (4 / CW);
+    constexpr size_t lds = (size_t)2 * S * kRS * sizeof(float);
+    auto kern = fc_step_kernel<MS, CW>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned tiles = (unsigned)((a.rows + S - 1) / S);
+    hipLaunchKernelGGL(kern, dim3(tiles, (unsigned)ycount), dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
+    FcStepLayout lay{};
+    lay.Q = Q; lay.d = d; lay.L = L;
+    lay.ring = Q > 1 ? Q - 1 : 1;
+    lay.Lk = (L + 7) / 8 * 8;
+    lay.nJB = (L + 31) / 32;
+    const int64_t Kall = (int64_t)lay.ring * lay.Lk + d + 1;
+    const int64_t KGtot = (Kall + 7) / 8;
+    // a step runs whole chunks of kPF groups and looks kPF groups ahead: both land in the zero tail
+    const int64_t KGpad = KGtot + 2 * kPF;
+    const int64_t bytes = (int64_t)lay.nJB * KGpad * 1024;
+    const int64_t row_bytes = (int64_t)lay.ring * lay.Lk * (int64_t)sizeof(float);
+    if (bytes >= ((int64_t)1 << 32) || row_bytes > ((int64_t)8 << 20)) return false;
+    lay.KGtot = (int)KGtot;
+    lay.KGpad = (int)KGpad;
+    lay.floats = (size_t)bytes / sizeof(float);
+    int64_t rows = ((((int64_t)2 << 30) - 1) / row_bytes) / 256 * 256;      // the buffer stays below 2^31 bytes
+    lay.chunk_rows = rows < 256 ? 256 : rows > 65536 ? 65536 : rows;
+    lay.hist_floats = (size_t)lay.chunk_rows * lay.ring * lay.Lk;
+    if (out != nullptr) *out = lay;
+    return true;
+}
+
+// Stack rows: slot s = 0 .. ring-1 holds lag ring - s (Lk rows, those beyond L zero), then W, b, zeros.
+// Fragment order: [column block][k-group][lane][e] with row = 8*group + 4*(lane>>5) + e, column = lane&31.
+void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out) {
+    const int L = lay.L, d = lay.d, Lk = lay.Lk;
+    const int64_t hist_rows = (int64_t)lay.ring * Lk;
+    for (size_t i = 0; i < lay.floats; ++i) out[i] = 0.0f;
+    for (int jb = 0; jb < lay.nJB; ++jb)
+        for (int kg = 0; kg < lay.KGtot; ++kg)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t k = (int64_t)kg * 8 + (lane >> 5) * 4 + e;
+                    const int j = jb * 32 + (lane & 31);
+                    if (j >= L) continue;
+                    float v = 0.0f;
+                    if (k < hist_rows) {
+                        const int s = (int)(k / Lk), mm = (int)(k - (int64_t)s * Lk);
+                        const int lag = lay.ring - s;
+                        if (mm < L) v = A[((size_t)(lag - 1) * L + mm) * L + j];
+                    } else if (k - hist_rows < d) {
+                        v = W[(size_t)(k - hist_rows) * L + j];
+                    } else if (k - hist_rows == d) {
+                        v = b[j];
+                    }
+                    out[(((size_t)jb * lay.KGpad + kg) * 64 + lane) * 4 + e] = v;
+                }
+}
+
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, const float* X,
+                                  int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+                                  hipStream_t stream) {
+    if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
+    const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
+    const int ycount = (lay.nJB + cw - 1) / cw;
+    const int64_t ldh = (int64_t)lay.ring * lay.Lk;
+    for (int64_t r0 = 0; r0 < N; r0 += lay.chunk_rows) {
+        const int64_t rows = (N - r0 < lay.chunk_rows) ? N - r0 : lay.chunk_rows;
+        for (int t = 1; t <= Q_run; ++t) {
+            FcStepArgs a{};
+            a.hist = hist; a.ldh = ldh; a.hist_bytes = (unsigned)(rows * ldh * (int64_t)sizeof(float));
+            a.X = X + r0 * ldx_n + (int64_t)(t - 1) * ldx_q; a.ldx_n = ldx_n;
+            a.Wp = Wp; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
+            a.Kh = (t - 1) * lay.Lk;
+            a.kg0 = (unsigned)((lay.ring - (t - 1)) * (lay.Lk / 8));
+            a.jb_stride = (unsigned)lay.KGpad * 1024u;
+            const int groups = (a.Kh + lay.d + 1 + 7) / 8;
+            a.nchunks = (groups + kPF - 1) / kPF;
+            a.d = lay.d; a.L = lay.L; a.nJB = lay.nJB; a.rows = (int)rows;
+            if (t == Q_run) {
+                a.out = H + r0 * lay.L; a.ldo = lay.L; a.ncols = lay.L;
+            } else {
+                a.out = hist + (int64_t)(t - 1) * lay.Lk; a.ldo = ldh; a.ncols = lay.Lk;
+            }
+            // 64-row blocks per wave while they still give every compute unit two work-groups
+            const bool big = cw > 1 && (rows + 64 * (4 / cw) - 1) / (64 * (4 / cw)) >= 512;
+            hipError_t e;
+            if (cw == 4) e = big ? launch_step<2, 4>(a, ycount, stream) : launch_step<1, 4>(a, ycount, stream);
+            else if (cw == 2) e = big ? launch_step<2, 2>(a, ycount, stream) : launch_step<1, 2>(a, ycount, stream);
+            else e = launch_step<1, 1>(a, ycount, stream);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+}  // namespace elm

@@ -31,6 +31,26 @@ void pack_weights(const PackedLayout& lay, const float* W, const float* U, const
 void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, const float* b, float* out);
 constexpr int kFcMaxK = 1272;      // contraction rows a 32-sample tile of the multi-lag cell can hold in LDS
 
+// ---- the fully connected multi-lag cell when the history of a window does not fit LDS: a launch per step,
+// the past states of a chunk of rows kept in a device buffer the model owns
+struct FcStepLayout {
+    int Q, d, L;
+    int ring;             // history slots per row (Q - 1, at least 1)
+    int Lk;               // slot width: L rounded up to 8 columns
+    int nJB;              // hidden-unit blocks of 32 columns
+    int KGtot;            // k-groups of 8 rows in the stack [A_{Q-1}; ...; A_1; W; b]
+    int KGpad;            // ... plus the zero groups the contraction may run or look into
+    size_t floats;        // packed stack: nJB * KGpad * 256
+    int64_t chunk_rows;   // rows the history buffer holds (a multiple of 256, at most 65,536)
+    size_t hist_floats;   // chunk_rows * ring * Lk
+};
+// false: the shape is out of range (stack of 4 GiB or more, or a history row above 8 MiB)
+bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
+void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, const float* X,
+                                  int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+                                  hipStream_t stream);
+
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
                          int64_t ldx_q, int64_t N, int Q_run, const float* h0, const float* c0,
                          float* H, float* C, hipStream_t stream);

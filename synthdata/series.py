@@ -59,6 +59,9 @@ EXTRA_CONFIGS = (
     ElmConfig("paper_elman", "elman_diag", 1_000_000, 50, 1, 100, 1, 0.3, 0.0, 0.0, False, 0.05, 13257),
     # the paper's fully connected multi-lag cell at Q = 10 (the window of most of its datasets), M = 100
     ElmConfig("paper_fc", "fc_multilag", 1_000_000, 10, 4, 100, 1, 0.1, 0.0, 0.0, False, 0.05, 13258),
+    # ... and at the window of its three largest datasets, Q = 50, with about their 70 % training share of
+    # 1e6 instances (the history of a window no longer fits on chip: one launch per step)
+    ElmConfig("paper_fc_q50", "fc_multilag", 700_000, 50, 4, 100, 1, 0.05, 0.0, 0.0, False, 0.05, 13259),
 )
 
 

@@ -41,6 +41,70 @@ def test_hidden_matches_oracle(elm, N, Q, d, L):
     model.close()
 
 
+# Windows whose history does not fit LDS take one launch per step over a device-resident history:
+# one, two and four column blocks per work-group, a short last group of column blocks (L = 300),
+# the widest input, slot widths that are not multiples of 8, ragged row tails, Q barely past the limit
+@pytest.mark.parametrize("N,Q,d,L", [
+    (100, 200, 1, 8), (257, 60, 2, 33), (90, 14, 1, 100), (70, 6, 1, 300), (40, 4, 64, 512),
+    (300, 50, 4, 100), (129, 50, 1, 50), (65, 300, 3, 5), (1, 130, 1, 10),
+])
+def test_hidden_per_step_path_matches_oracle(elm, N, Q, d, L):
+    assert (Q - 1) * L + d + 1 > 1272
+    W, A, b = weights(Q, d, L, seed=N + Q + L)
+    X = np.random.default_rng(N * 3 + Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
+    Xd = torch.from_numpy(X).cuda()
+    H = elm.hidden(model, Xd).cpu().numpy()
+    assert h_close(H, ocells.hidden_fc_multilag(X, W, A, b))
+    for q in {1, 2, Q // 2, Q - 1}:
+        got = elm.hidden(model, Xd, Q_run=q).cpu().numpy()
+        assert h_close(got, ocells.hidden_fc_multilag(X, W, A, b, steps=q)), q
+    model.close()
+
+
+# Launches large enough for 64-row blocks per wave, and more rows than the history buffer holds
+# (65,536 here: the rest is a second pass over the steps); rows are independent, so the oracle
+# is evaluated on samples: the first and last rows and those around the pass boundary
+@pytest.mark.parametrize("N,Q,d,L", [(70_000, 21, 1, 64), (40_000, 14, 2, 100), (66_000, 160, 1, 8)])
+def test_hidden_per_step_path_many_rows(elm, N, Q, d, L):
+    W, A, b = weights(Q, d, L, seed=Q + L)
+    X = np.random.default_rng(Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
+    H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    model.close()
+    idx = np.unique(np.concatenate([np.arange(0, 200), np.arange(N - 200, N),
+                                    np.clip(np.arange(65_536 - 150, 65_536 + 150), 0, N - 1),
+                                    np.random.default_rng(1).integers(0, N, 300)]))
+    assert h_close(H[idx], ocells.hidden_fc_multilag(X[idx], W, A, b))
+    assert np.all(np.isfinite(H)) and np.abs(H).max() <= 1.0
+
+
+def test_fit_per_step_path_matches_oracle_fit(elm):
+    N, Q, d, L, m, seed = 20000, 50, 2, 30, 2, 12
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    T = (np.sin(X[:, -8:].sum(axis=(1, 2)))[:, None] * np.arange(1, m + 1) + 0.05 * rng.standard_normal((N, m))
+         ).astype(np.float32)
+    w_scale = 0.08
+    Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(T).cuda()
+    res = elm.fit("fc_multilag", Xd, Td, L, seed=seed, w_scale=w_scale)
+    ref = ofit.fit("fc_multilag", X, T, L, seed, w_scale=w_scale)
+    W, U, b, beta = res.model.weights()
+    assert np.array_equal(W, ref["W"]) and np.array_equal(U, ref["U"]) and np.array_equal(b, ref["b"])
+    assert h_close(res.H.cpu().numpy(), ref["H"])
+    assert abs(res.stats.rmse - ref["rmse"]) <= 1e-4 * ref["rmse"]
+    assert lstsq.normal_equation_residual(res.H.cpu().numpy(), T, beta) <= 1e-5
+    Y = elm.predict(res.model, Xd[:700]).cpu().numpy()
+    np.testing.assert_allclose(Y, ref["H"][:700] @ beta, rtol=0,
+                               atol=2e-5 * np.abs(beta).sum(axis=0).max() + 1e-5)
+    res.model.close()
+    # the streamed fit recomputes H chunk by chunk through the same per-step launches
+    st = elm.fit_streamed("fc_multilag", Xd, Td, L, seed=seed, w_scale=w_scale, chunk_rows=4096)
+    assert abs(st.stats.rmse - ref["rmse"]) <= 1e-4 * ref["rmse"]
+    assert lstsq.normal_equation_residual(ref["H"], T, st.model.weights()[3]) <= 1e-5
+    st.model.close()
+
+
 def test_fewer_steps_lag_one_only_and_diagonal_lags(elm):
     Q, d, L, N = 9, 2, 40, 700
     W, A, b = weights(Q, d, L, seed=5)
@@ -104,5 +168,5 @@ def test_argument_errors(elm):
     assert ei.value.code == -5
     model.close()
     with pytest.raises(elm.ElmRnnError) as ei:
-        elm.Model.create("fc_multilag", 50, 1, 100, 1, seed=1)        # 49 * 100 history columns
+        elm.Model.create("fc_multilag", 4098, 1, 512, 1, seed=1)      # a history row above 8 MiB
     assert ei.value.code == -5

@@ -71,6 +71,26 @@ def test_random_shape(elm, seed):
     model.close()
 
 
+# the fully connected multi-lag cell where a window's history leaves the chip (a launch per step)
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shape_multilag_launch_per_step(elm, seed):
+    rng = np.random.default_rng(3000 + seed)
+    Q = int(rng.choice([rng.integers(3, 12), rng.integers(12, 80)]))
+    L = int(rng.integers(max(1, 1300 // (Q - 1) + 1), min(513, max(3, 6000 // (Q - 1))) + 1))
+    d = int(rng.choice([rng.integers(1, 9), rng.integers(9, 65)]))
+    N = int(rng.choice([rng.integers(1, 200), rng.integers(200, 1500)]))
+    q_run = int(rng.choice([Q, rng.integers(1, Q + 1)]))
+    assert (Q - 1) * L + d + 1 > 1272
+    W, U, b = make_weights(rng, "fc_multilag", Q, d, L)
+    X = rng.uniform(-1, 1, (N, Q, d)).astype(np.float32)
+    print(f"case: N={N} Q={Q} d={d} L={L} Q_run={q_run}", flush=True)
+    model = elm.Model.from_weights("fc_multilag", Q, 1, W, U, b)
+    H = elm.hidden(model, torch.from_numpy(X).cuda(), Q_run=q_run).cpu().numpy()
+    ok, worst = h_close(H, ocells.hidden_fc_multilag(X, W, U, b, steps=q_run))
+    assert ok, (N, Q, d, L, q_run, worst)
+    model.close()
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_long_window_of_the_papers_elman_cell(elm, seed):
     """Window lengths across the slot counts of the long-window kernel (129 .. 4096 steps)."""
