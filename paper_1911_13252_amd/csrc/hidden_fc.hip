@@ -3,11 +3,11 @@
 //
 //   h(t) = tanh( [h(1) | h(2) | ... | h(t-1) | x_t | 1] . [A_{t-1}; A_{t-2}; ...; A_1; W; b] )
 //
-// The states of a chunk of rows are kept in time order in a device buffer (row stride (Q-1)*Lk, a slot
-// of Lk = L rounded up to 8 columns per step), so the operand of step t is a prefix of the row followed
-// by the input, and its weights are a suffix of one stack [A_{Q-1}; ...; A_1; W; b]: nothing is
-// shifted or rotated, every step is a plain (rows x K_t) . (K_t x L) contraction with K_t growing by
-// Lk per step.  A work-group streams its rows of the operand through LDS in chunks of 64 columns
+// The states of a pass of rows are kept in time order in a device buffer ([slot][row][Lk], one slot of
+// Lk = L rounded up to 8 columns per step: a tile's rows of a slot are contiguous in memory), so the
+// operand of step t is the first t-1 slots followed by the input, and its weights are a suffix of one
+// stack [A_{Q-1}; ...; A_1; W; b]: nothing is shifted or rotated, every step is a plain
+// (rows x K_t) . (K_t x L) contraction with K_t growing by Lk per step.  A work-group streams its rows of the operand through LDS in chunks of 64 columns
 // (double-buffered, global loads one chunk ahead in registers); every wave owns a 32-column block of
 // the output and reads its weight fragments straight from L2 in a pre-packed order, eight k-groups
 // ahead.  The history is read once per step: (t-1)*Lk*4 bytes per row against 2*(t-1)*Lk*L flops.
@@ -28,9 +28,10 @@ constexpr int kRS = kBK + 4;       // LDS row stride in floats (conflict-free 16
 constexpr int kPF = 8;             // weight k-groups in flight per wave = one chunk
 
 struct FcStepArgs {
-    const float* hist;     // [rows][ldh]: h(1) .. h(t-1) of this chunk of rows
-    int64_t ldh;
-    unsigned hist_bytes;   // rows * ldh * 4 (below 2^31)
+    const float* hist;     // [slot][row][Lk]: slot s holds h(s+1) of this pass's rows
+    unsigned slot_floats;  // distance between slots: rows of a full pass * Lk
+    unsigned hist_bytes;   // ring * slot_floats * 4 (below 2^31)
+    int Lk;
     const float* X;        // x_t of the chunk's first row
     int64_t ldx_n;
     const float* Wp;       // packed weight stack
@@ -41,7 +42,7 @@ struct FcStepArgs {
     int Kh;                // history columns of this step, (t-1)*Lk
     int d, L, nJB;
     int rows;
-    float* out;            // history slot t-1 (ldo = ldh) or H (ldo = L)
+    float* out;            // history slot t-1 (ldo = Lk) or H (ldo = L)
     int64_t ldo;
     int ncols;             // columns stored per row; those at or beyond L are zeros
 };
@@ -66,31 +67,38 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
     const int lr = tid >> 4, lk = (tid & 15) * 4;
     const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(p.hist), 0, (int)p.hist_bytes, 0x00020000);
-    unsigned hoff[NLD];                        // byte offset of the piece in chunk 0; rows past the end: out of range
+    unsigned hoff[NLD];                        // byte offset of the piece's row inside a slot; rows past the end: out of range
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
         const int64_t row = row0 + lr + 16 * q;
-        hoff[q] = row < p.rows ? (unsigned)((row * p.ldh + lk) * 4) : 0xFFFFFFF0u;
+        hoff[q] = row < p.rows ? (unsigned)(row * p.Lk * 4) : 0xFFFFFFF0u;
     }
+    // operand column k lies in slot k / Lk; Lk and k are multiples of 4, so a piece stays inside a slot
+    auto slot_offset = [&](int k) {
+        const int sl = k / p.Lk;
+        return ((unsigned)sl * p.slot_floats + (unsigned)(k - sl * p.Lk)) * 4u;
+    };
     floatx4 stage[NLD];
     // a chunk that lies inside the history: range-checked loads, rows past the end read as zero
     auto load_history = [&](int c) {
+        const unsigned so = slot_offset(c * kBK + lk);
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
-            const unsigned off = hoff[q] == 0xFFFFFFF0u ? hoff[q] : hoff[q] + (unsigned)c * (kBK * 4u);
+            const unsigned off = hoff[q] == 0xFFFFFFF0u ? hoff[q] : hoff[q] + so;
             stage[q] = buffer_load_x4(hrs, off, 0);
         }
     };
     // a chunk that holds the end of the history, x_t, the constant 1 and the zero padding
     auto load_edge = [&](int c) {
         const int k = c * kBK + lk;
+        const unsigned so = k < p.Kh ? slot_offset(k) : 0u;
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
             const int64_t row = row0 + lr + 16 * q;
             floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
             if (row < p.rows) {
                 if (k < p.Kh) {            // Kh and k are multiples of 4: a piece never straddles the edge
-                    v = *reinterpret_cast<const floatx4*>(p.hist + row * p.ldh + k);
+                    v = buffer_load_x4(hrs, hoff[q] + so, 0);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -253,12 +261,15 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
     if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
     const int ycount = (lay.nJB + cw - 1) / cw;
-    const int64_t ldh = (int64_t)lay.ring * lay.Lk;
-    for (int64_t r0 = 0; r0 < N; r0 += lay.chunk_rows) {
-        const int64_t rows = (N - r0 < lay.chunk_rows) ? N - r0 : lay.chunk_rows;
+    // passes of equal size (a multiple of 256 rows) rather than full buffers and a short last one
+    const int64_t passes = (N + lay.chunk_rows - 1) / lay.chunk_rows;
+    const int64_t per_pass = ((N + passes - 1) / passes + 255) / 256 * 256;
+    for (int64_t r0 = 0; r0 < N; r0 += per_pass) {
+        const int64_t rows = (N - r0 < per_pass) ? N - r0 : per_pass;
         for (int t = 1; t <= Q_run; ++t) {
             FcStepArgs a{};
-            a.hist = hist; a.ldh = ldh; a.hist_bytes = (unsigned)(rows * ldh * (int64_t)sizeof(float));
+            a.hist = hist; a.Lk = lay.Lk; a.slot_floats = (unsigned)(per_pass * lay.Lk);
+            a.hist_bytes = (unsigned)((int64_t)lay.ring * per_pass * lay.Lk * (int64_t)sizeof(float));
             a.X = X + r0 * ldx_n + (int64_t)(t - 1) * ldx_q; a.ldx_n = ldx_n;
             a.Wp = Wp; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
             a.Kh = (t - 1) * lay.Lk;
@@ -270,7 +281,7 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
             if (t == Q_run) {
                 a.out = H + r0 * lay.L; a.ldo = lay.L; a.ncols = lay.L;
             } else {
-                a.out = hist + (int64_t)(t - 1) * lay.Lk; a.ldo = ldh; a.ncols = lay.Lk;
+                a.out = hist + (int64_t)(t - 1) * per_pass * lay.Lk; a.ldo = lay.Lk; a.ncols = lay.Lk;
             }
             // 64-row blocks per wave while they still give every compute unit two work-groups
             const bool big = cw > 1 && (rows + 64 * (4 / cw) - 1) / (64 * (4 / cw)) >= 512;

@@ -63,17 +63,19 @@ def test_hidden_per_step_path_matches_oracle(elm, N, Q, d, L):
 
 
 # Launches large enough for 64-row blocks per wave, and more rows than the history buffer holds
-# (65,536 here: the rest is a second pass over the steps); rows are independent, so the oracle
-# is evaluated on samples: the first and last rows and those around the pass boundary
-@pytest.mark.parametrize("N,Q,d,L", [(70_000, 21, 1, 64), (40_000, 14, 2, 100), (66_000, 160, 1, 8)])
+# (65,536 here: the rows are then taken in equal passes over the steps); rows are independent, so the
+# oracle is evaluated on samples: the first and last rows and those around the pass boundary
+@pytest.mark.parametrize("N,Q,d,L", [(131_000, 21, 1, 64), (40_000, 14, 2, 100), (50_001, 15, 1, 97), (66_000, 160, 1, 8)])
 def test_hidden_per_step_path_many_rows(elm, N, Q, d, L):
     W, A, b = weights(Q, d, L, seed=Q + L)
     X = np.random.default_rng(Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
     H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
     model.close()
+    passes = -(-N // 65_536)
+    edge = -(-(-(-N // passes)) // 256) * 256          # the passes are equal multiples of 256 rows
     idx = np.unique(np.concatenate([np.arange(0, 200), np.arange(N - 200, N),
-                                    np.clip(np.arange(65_536 - 150, 65_536 + 150), 0, N - 1),
+                                    np.clip(np.arange(edge - 150, edge + 150), 0, N - 1),
                                     np.random.default_rng(1).integers(0, N, 300)]))
     assert h_close(H[idx], ocells.hidden_fc_multilag(X[idx], W, A, b))
     assert np.all(np.isfinite(H)) and np.abs(H).max() <= 1.0
