@@ -1,5 +1,6 @@
 """GPU parity at the full sizes of the study workloads, in the launch configuration bench.py times:
-the paper's own two cells at a million windows and its Elman cell on the shape of its longest dataset
+the paper's own two cells at a million windows (the fully connected one also at Q = 50, where every step
+is a launch over a device-resident history) and its Elman cell on the shape of its longest dataset
 (4,500 windows of 3,197 steps, 100 units).  The oracle computes sampled rows one by one."""
 import numpy as np
 import pytest
@@ -22,7 +23,7 @@ def sliding(series, N, Q, d):
     return dev, torch.as_strided(dev, (N, Q, d), (d, d, 1))          # zero-copy windows, as bench.py --sweep
 
 
-@pytest.mark.parametrize("name", ["paper_elman", "paper_fc"])
+@pytest.mark.parametrize("name", ["paper_elman", "paper_fc", "paper_fc_q50"])
 def test_paper_cells_at_a_million_windows(elm, name):
     cfg = synthdata.get_config(name)
     series = synthdata.make_series(cfg.N + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
@@ -30,7 +31,9 @@ def test_paper_cells_at_a_million_windows(elm, name):
     model = elm.Model.create(cfg.cell, cfg.Q, cfg.d, cfg.L, cfg.m, seed=cfg.seed, w_scale=cfg.w_scale)
     H = elm.hidden(model, X)
     assert torch.isfinite(H).all()
-    rows = np.unique(np.concatenate([np.arange(70), np.random.default_rng(1).choice(cfg.N, 400), [cfg.N - 1]]))
+    # (for paper_fc_q50 the rows come in 11 passes of 63,744: the samples include both sides of the first edges)
+    rows = np.unique(np.concatenate([np.arange(70), np.random.default_rng(1).choice(cfg.N, 400), [cfg.N - 1],
+                                     np.arange(63_744 - 40, 63_744 + 40), np.arange(2 * 63_744 - 40, 2 * 63_744 + 40)]))
     Xs = np.lib.stride_tricks.sliding_window_view(series, (cfg.Q, cfg.d))[rows, 0]
     W, U, b, _ = model.weights()
     ref = ocells.hidden(cfg.cell, Xs, W, U, b)
