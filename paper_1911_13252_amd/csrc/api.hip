@@ -20,6 +20,7 @@ struct elm_rnn_model {
     elm::FcStepLayout fcs{};      // ELM_CELL_FC_MULTILAG beyond what LDS holds: one launch per step with
     float* dFcW = nullptr;        //   the packed stack [A_{Q-1}; ...; A_1; W; b] and
     float* dFcHist = nullptr;     //   the past states of a chunk of rows (scratch of every hidden-matrix call)
+    float* dFcSums = nullptr;     //   and, for layers of at most 64 units, the carried sums of a block of steps
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
     void* dWs = nullptr;
@@ -172,6 +173,8 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         if (e == hipSuccess) e = hipMemcpy(mdl->dTiny, tiny.data(), tiny.size() * sizeof(float), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcHist, mdl->fcs.hist_floats * sizeof(float));
+    if (e == hipSuccess && dst == &mdl->dFcW && mdl->fcs.nJB <= 2)
+        e = hipMalloc(&mdl->dFcSums, (size_t)mdl->fcs.chunk_rows * 128 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
@@ -210,7 +213,8 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
                                   stream);
     }
     if (mdl->dFcW != nullptr)
-        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcHist, X, ldx_n, ldx_q, N, Q_run, H, stream);
+        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcHist, mdl->dFcSums, X, ldx_n, ldx_q, N, Q_run, H,
+                                      stream);
     if (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dTiny != nullptr)
         return launch_hidden_tiny(mdl->cell, mdl->d, mdl->L, mdl->dTiny, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     if (mdl->contraction == ELM_CONTRACT_SPLIT16 && mdl->dWs != nullptr)
@@ -375,6 +379,7 @@ void elm_rnn_free(elm_rnn_model* model) {
     if (model->dDiag) (void)hipFree(model->dDiag);
     if (model->dFcW) (void)hipFree(model->dFcW);
     if (model->dFcHist) (void)hipFree(model->dFcHist);
+    if (model->dFcSums) (void)hipFree(model->dFcSums);
     if (model->dWs) (void)hipFree(model->dWs);
     if (model->dBeta) (void)hipFree(model->dBeta);
     delete model;

@@ -45,22 +45,37 @@ struct FcStepArgs {
     float* out;            // history slot t-1 (ldo = Lk) or H (ldo = L)
     int64_t ldo;
     int ncols;             // columns stored per row; those at or beyond L are zeros
+    // Layers of one or two column blocks take the steps in blocks of nsteps = 4 / nJB: one launch
+    // contracts the finished slots for all steps of the block at once (wave w: step w / nJB of the block,
+    // column block w % nJB; the weights of consecutive steps start one slot apart in the stack) and stores
+    // the raw sums; the launch of each step then starts from its sums and adds the block's own slots.
+    int block;             // 1: the block launch (no input columns, raw sums out, [row][step][32 nJB])
+    int nsteps;            // steps it covers (1 otherwise)
+    unsigned slot_groups;  // k-groups per slot, Lk / 8
+    const float* acc_in;   // sums the accumulators start from (row stride ldacc), or null
+    int64_t ldacc;
 };
 
-// MS 32-row blocks per wave, CW column blocks per work-group (the other 4/CW waves take further rows)
-template <int MS, int CW>
+// MS 32-row blocks per wave, CW column blocks per work-group (the other 4/CW waves take further rows);
+// EXT: the launch may be a block launch or start from carried sums (layers of at most 64 units only: the
+// plain form keeps its registers for four work-groups per compute unit)
+template <int MS, int CW, bool EXT>
 __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p) {
+    const bool block = EXT && p.block != 0;
     constexpr int WR = 4 / CW, S = 32 * MS * WR, NLD = S / 16;
     extern __shared__ float lds[];             // [2][S][kRS]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wcol = wave % CW, rbase = (wave / CW) * 32 * MS;
-    const int jb = (int)blockIdx.y * CW + wcol;
-    const bool active = jb < p.nJB;            // the last group of column blocks may be short
+    const int unit = (int)blockIdx.y * CW + wcol;
+    const int jstep = block ? unit / p.nJB : 0;            // step of the block (block launch only)
+    const int jb = unit - jstep * p.nJB;
+    const bool active = unit < p.nJB * p.nsteps;   // the last group of column blocks may be short
     const int64_t row0 = (int64_t)blockIdx.x * S;
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(p.Wp), 0, (int)p.wp_bytes, 0x00020000);   // raw dword buffer, range-checked
-    const unsigned wbase = (unsigned)(active ? jb : 0) * p.jb_stride + p.kg0 * 1024u;
+    const unsigned wbase = active ? (unsigned)jb * p.jb_stride + (p.kg0 - (unsigned)jstep * p.slot_groups) * 1024u
+                                  : p.kg0 * 1024u;
     const unsigned voff = (unsigned)lane * 16u;
 
     // this thread's NLD 16-byte pieces of a chunk: row (tid>>4) + 16*q, columns 4*(tid&15) .. +3
@@ -103,7 +118,7 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int kk = k + e - p.Kh;
-                        v[e] = kk < p.d ? p.X[row * p.ldx_n + kk] : (kk == p.d ? 1.0f : 0.0f);
+                        if (!block) v[e] = kk < p.d ? p.X[row * p.ldx_n + kk] : (kk == p.d ? 1.0f : 0.0f);
                     }
                 }
             }
@@ -120,7 +135,11 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[ms][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) {
+            const int64_t row = row0 + rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            acc[ms][i] = (EXT && p.acc_in != nullptr && active && row < p.rows)
+                             ? p.acc_in[row * p.ldacc + jb * 32 + (lane & 31)] : 0.0f;
+        }
 
     floatx4 bq[kPF];
 #pragma unroll
@@ -177,6 +196,16 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
 
     if (!active) return;
     const int col = jb * 32 + (lane & 31);
+    if (block) {                               // raw sums of step jstep of the block, all 32 columns of the block
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = row0 + rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                if (row < p.rows) p.out[row * p.ldo + jstep * 32 * p.nJB + col] = acc[ms][i];
+            }
+        return;
+    }
     if (col >= p.ncols) return;
     const bool real = col < p.L;
 #pragma unroll
@@ -188,11 +217,11 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
         }
 }
 
-template <int MS, int CW>
+template <int MS, int CW, bool EXT = false>
 hipError_t launch_step(const FcStepArgs& a, int ycount, hipStream_t stream) {
     constexpr int S = 32 * MS * (4 / CW);
     constexpr size_t lds = (size_t)2 * S * kRS * sizeof(float);
-    auto kern = fc_step_kernel<MS, CW>;
+    auto kern = fc_step_kernel<MS, CW, EXT>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -222,6 +251,8 @@ bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
     lay.KGpad = (int)KGpad;
     lay.floats = (size_t)bytes / sizeof(float);
     int64_t rows = ((((int64_t)2 << 30) - 1) / row_bytes) / 256 * 256;      // the buffer stays below 2^31 bytes
+    // 65,536 rows are two full rounds of 64-row work-groups at two per compute unit; larger passes measured
+    // slower (100,096 rows: three rounds and a fraction), and so did 49,152 (one and a half)
     lay.chunk_rows = rows < 256 ? 256 : rows > 65536 ? 65536 : rows;
     lay.hist_floats = (size_t)lay.chunk_rows * lay.ring * lay.Lk;
     if (out != nullptr) *out = lay;
@@ -255,41 +286,70 @@ void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float*
                 }
 }
 
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, const float* X,
-                                  int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, float* sums,
+                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream) {
     if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
     const int ycount = (lay.nJB + cw - 1) / cw;
+    // steps per block: the waves that a layer of one or two column blocks leaves free take further steps
+    const int B = (sums != nullptr && lay.nJB <= 2) ? 4 / lay.nJB : 1;
+    const int ldsums = 128;                    // [row][B][32 nJB]
     // passes of equal size (a multiple of 256 rows) rather than full buffers and a short last one
     const int64_t passes = (N + lay.chunk_rows - 1) / lay.chunk_rows;
     const int64_t per_pass = ((N + passes - 1) / passes + 255) / 256 * 256;
+    const int64_t slot_floats = per_pass * lay.Lk;
     for (int64_t r0 = 0; r0 < N; r0 += per_pass) {
         const int64_t rows = (N - r0 < per_pass) ? N - r0 : per_pass;
-        for (int t = 1; t <= Q_run; ++t) {
-            FcStepArgs a{};
-            a.hist = hist; a.Lk = lay.Lk; a.slot_floats = (unsigned)(per_pass * lay.Lk);
-            a.hist_bytes = (unsigned)((int64_t)lay.ring * per_pass * lay.Lk * (int64_t)sizeof(float));
-            a.X = X + r0 * ldx_n + (int64_t)(t - 1) * ldx_q; a.ldx_n = ldx_n;
-            a.Wp = Wp; a.wp_bytes = (unsigned)(lay.floats * sizeof(float));
-            a.Kh = (t - 1) * lay.Lk;
-            a.kg0 = (unsigned)((lay.ring - (t - 1)) * (lay.Lk / 8));
-            a.jb_stride = (unsigned)lay.KGpad * 1024u;
-            const int groups = (a.Kh + lay.d + 1 + 7) / 8;
-            a.nchunks = (groups + kPF - 1) / kPF;
-            a.d = lay.d; a.L = lay.L; a.nJB = lay.nJB; a.rows = (int)rows;
-            if (t == Q_run) {
-                a.out = H + r0 * lay.L; a.ldo = lay.L; a.ncols = lay.L;
-            } else {
-                a.out = hist + (int64_t)(t - 1) * per_pass * lay.Lk; a.ldo = lay.Lk; a.ncols = lay.Lk;
+        FcStepArgs base{};
+        base.Lk = lay.Lk; base.slot_floats = (unsigned)slot_floats; base.slot_groups = (unsigned)(lay.Lk / 8);
+        base.ldx_n = ldx_n; base.Wp = Wp; base.wp_bytes = (unsigned)(lay.floats * sizeof(float));
+        base.jb_stride = (unsigned)lay.KGpad * 1024u;
+        base.d = lay.d; base.L = lay.L; base.nJB = lay.nJB; base.rows = (int)rows;
+        base.nsteps = 1; base.ldacc = ldsums;
+        for (int t0 = 0; t0 < Q_run; t0 += B) {
+            const int nb = Q_run - t0 < B ? Q_run - t0 : B;
+            const bool carried = B > 1 && t0 > 0;
+            if (carried) {
+                // the finished slots 0 .. t0-1 into the sums of steps t0+1 .. t0+nb
+                FcStepArgs a = base;
+                a.hist = hist; a.hist_bytes = (unsigned)(lay.ring * slot_floats * (int64_t)sizeof(float));
+                a.X = X;                                   // not read
+                a.Kh = t0 * lay.Lk;
+                a.kg0 = (unsigned)((lay.ring - t0) * (lay.Lk / 8));      // step t0+1; step t0+j starts j-1 slots earlier
+                a.nchunks = (a.Kh + kBK - 1) / kBK;
+                a.block = 1; a.nsteps = nb;
+                a.out = sums; a.ldo = ldsums; a.ncols = ldsums;
+                const hipError_t e = (rows + 63) / 64 >= 512 ? launch_step<2, 4, true>(a, 1, stream)
+                                                             : launch_step<1, 4, true>(a, 1, stream);
+                if (e != hipSuccess) return e;
             }
-            // 64-row blocks per wave while they still give every compute unit two work-groups
-            const bool big = cw > 1 && (rows + 64 * (4 / cw) - 1) / (64 * (4 / cw)) >= 512;
-            hipError_t e;
-            if (cw == 4) e = big ? launch_step<2, 4>(a, ycount, stream) : launch_step<1, 4>(a, ycount, stream);
-            else if (cw == 2) e = big ? launch_step<2, 2>(a, ycount, stream) : launch_step<1, 2>(a, ycount, stream);
-            else e = launch_step<1, 1>(a, ycount, stream);
-            if (e != hipSuccess) return e;
+            for (int j = 1; j <= nb; ++j) {
+                const int t = t0 + j;
+                const int own = carried ? j - 1 : t - 1;   // slots this launch contracts itself: t-1-own .. t-2
+                const int first = t - 1 - own;
+                FcStepArgs a = base;
+                a.hist = hist + (int64_t)first * slot_floats;
+                a.hist_bytes = (unsigned)((lay.ring - first) * slot_floats * (int64_t)sizeof(float));
+                a.X = X + r0 * ldx_n + (int64_t)(t - 1) * ldx_q;
+                a.Kh = own * lay.Lk;
+                a.kg0 = (unsigned)((lay.ring - own) * (lay.Lk / 8));
+                const int groups = (a.Kh + lay.d + 1 + 7) / 8;
+                a.nchunks = (groups + kPF - 1) / kPF;
+                a.acc_in = carried ? sums + (j - 1) * 32 * lay.nJB : nullptr;
+                if (t == Q_run) {
+                    a.out = H + r0 * lay.L; a.ldo = lay.L; a.ncols = lay.L;
+                } else {
+                    a.out = hist + (int64_t)(t - 1) * slot_floats; a.ldo = lay.Lk; a.ncols = lay.Lk;
+                }
+                // 64-row blocks per wave while they still give every compute unit two work-groups
+                const bool big = cw > 1 && (rows + 64 * (4 / cw) - 1) / (64 * (4 / cw)) >= 512;
+                hipError_t e;
+                if (cw == 4) e = big ? launch_step<2, 4>(a, ycount, stream) : launch_step<1, 4>(a, ycount, stream);
+                else if (cw == 2) e = big ? launch_step<2, 2, true>(a, ycount, stream) : launch_step<1, 2, true>(a, ycount, stream);
+                else e = launch_step<1, 1, true>(a, ycount, stream);
+                if (e != hipSuccess) return e;
+            }
         }
     }
     return hipSuccess;

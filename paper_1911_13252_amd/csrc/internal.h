@@ -47,8 +47,9 @@ struct FcStepLayout {
 // false: the shape is out of range (stack of 4 GiB or more, or a history row above 8 MiB)
 bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
 void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, const float* X,
-                                  int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+// sums: chunk_rows x 128 floats of scratch for layers of at most 64 units (steps taken in blocks), else null
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, float* sums,
+                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream);
 
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,

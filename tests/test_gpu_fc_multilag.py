@@ -62,21 +62,32 @@ def test_hidden_per_step_path_matches_oracle(elm, N, Q, d, L):
     model.close()
 
 
-# Launches large enough for 64-row blocks per wave, and more rows than the history buffer holds
-# (65,536 here: the rows are then taken in equal passes over the steps); rows are independent, so the
-# oracle is evaluated on samples: the first and last rows and those around the pass boundary
-@pytest.mark.parametrize("N,Q,d,L", [(131_000, 21, 1, 64), (40_000, 14, 2, 100), (50_001, 15, 1, 97), (66_000, 160, 1, 8)])
-def test_hidden_per_step_path_many_rows(elm, N, Q, d, L):
+def pass_rows(N, Q, L):
+    """Rows per pass of the launch-per-step form: the history buffer stays below 2 GiB and holds at most
+    65,536 rows; the passes are equal multiples of 256 rows."""
+    row_bytes = max(Q - 1, 1) * (-(-L // 8) * 8) * 4
+    cap = min(65_536, max(256, (2 ** 31 - 1) // row_bytes // 256 * 256))
+    passes = -(-N // cap)
+    return -(-(-(-N // passes)) // 256) * 256
+
+
+# Launches large enough for 64-row blocks per wave, and more rows than the history buffer holds (the rows
+# are then taken in equal passes over the steps); rows are independent, so the oracle is evaluated on
+# samples: the first and last rows, those around the pass boundary and random ones
+@pytest.mark.parametrize("N,Q,d,L,ns", [(131_000, 21, 1, 64, 200), (40_000, 14, 2, 100, 200), (50_001, 15, 1, 97, 200),
+                                        (66_000, 160, 1, 8, 150), (60_000, 100, 1, 100, 40)])
+def test_hidden_per_step_path_many_rows(elm, N, Q, d, L, ns):
     W, A, b = weights(Q, d, L, seed=Q + L)
     X = np.random.default_rng(Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
     H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
     model.close()
-    passes = -(-N // 65_536)
-    edge = -(-(-(-N // passes)) // 256) * 256          # the passes are equal multiples of 256 rows
-    idx = np.unique(np.concatenate([np.arange(0, 200), np.arange(N - 200, N),
-                                    np.clip(np.arange(edge - 150, edge + 150), 0, N - 1),
-                                    np.random.default_rng(1).integers(0, N, 300)]))
+    edge = pass_rows(N, Q, L)
+    if (N, Q, L) in ((131_000, 21, 64), (66_000, 160, 8), (60_000, 100, 100)):
+        assert edge < N                              # these two cases take two passes
+    idx = np.unique(np.concatenate([np.arange(0, ns), np.arange(N - ns, N),
+                                    np.clip(np.arange(edge - ns, edge + ns), 0, N - 1),
+                                    np.random.default_rng(1).integers(0, N, ns)]))
     assert h_close(H[idx], ocells.hidden_fc_multilag(X[idx], W, A, b))
     assert np.all(np.isfinite(H)) and np.abs(H).max() <= 1.0
 
