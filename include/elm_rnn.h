@@ -65,7 +65,7 @@ extern "C" {
                                 states that the model owns (allocated at creation, below 2 GiB: room for
                                 up to 65,536 rows, more rows are taken in passes).  Calls that build H
                                 from one such model must not overlap in time (they share that buffer).
-                                ELM_EUNSUPPORTED if a window's history exceeds 8 MiB or the packed lag
+                                ELM_EUNSUPPORTED if a window's history reaches 8 MiB or the packed lag
                                 matrices 4 GiB                                                       */
 
 /* How the dense cells carry the recurrent contraction h_{t-1} U of each step (the input part x_t W + b

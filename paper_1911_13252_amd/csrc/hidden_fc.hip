@@ -7,10 +7,11 @@
 // Lk = L rounded up to 8 columns per step: a tile's rows of a slot are contiguous in memory), so the
 // operand of step t is the first t-1 slots followed by the input, and its weights are a suffix of one
 // stack [A_{Q-1}; ...; A_1; W; b]: nothing is shifted or rotated, every step is a plain
-// (rows x K_t) . (K_t x L) contraction with K_t growing by Lk per step.  A work-group streams its rows of the operand through LDS in chunks of 64 columns
-// (double-buffered, global loads one chunk ahead in registers); every wave owns a 32-column block of
-// the output and reads its weight fragments straight from L2 in a pre-packed order, eight k-groups
-// ahead.  The history is read once per step: (t-1)*Lk*4 bytes per row against 2*(t-1)*Lk*L flops.
+// (rows x K_t) . (K_t x L) contraction with K_t growing by Lk per step.  A work-group streams its rows
+// of the operand through LDS in chunks of 64 columns (double-buffered, global loads one chunk ahead in
+// registers); every wave owns a 32-column block of the output and reads its weight fragments straight
+// from L2 in a pre-packed order, eight k-groups ahead.  The history is read once per step ((t-1)*Lk*4
+// bytes per row against 2*(t-1)*Lk*L flops), or once per block of steps for layers of at most 64 units.
 //
 // The paper's kernel keeps the history of one (sample, neuron) pair per thread (its H_loc) and so
 // re-reads every other neuron's past outputs from global memory per thread; here a step is one
@@ -246,7 +247,8 @@ bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
     const int64_t KGpad = KGtot + 2 * kPF;
     const int64_t bytes = (int64_t)lay.nJB * KGpad * 1024;
     const int64_t row_bytes = (int64_t)lay.ring * lay.Lk * (int64_t)sizeof(float);
-    if (bytes >= ((int64_t)1 << 32) || row_bytes > ((int64_t)8 << 20)) return false;
+    // 256 rows of history must stay below 2^31 bytes (32-bit offsets into a range-checked buffer)
+    if (bytes >= ((int64_t)1 << 32) || row_bytes >= ((int64_t)8 << 20)) return false;
     lay.KGtot = (int)KGtot;
     lay.KGpad = (int)KGpad;
     lay.floats = (size_t)bytes / sizeof(float);

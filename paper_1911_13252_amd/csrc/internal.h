@@ -44,7 +44,7 @@ struct FcStepLayout {
     int64_t chunk_rows;   // rows the history buffer holds (a multiple of 256, at most 65,536)
     size_t hist_floats;   // chunk_rows * ring * Lk
 };
-// false: the shape is out of range (stack of 4 GiB or more, or a history row above 8 MiB)
+// false: the shape is out of range (stack of 4 GiB or more, or a history row of 8 MiB or more)
 bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
 void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
 // sums: chunk_rows x 128 floats of scratch for layers of at most 64 units (steps taken in blocks), else null
