@@ -147,6 +147,15 @@ def run_sweep(elm, torch, steps: int) -> dict:
         r["study"] = "long windows"
         r["stage1_tflops"] = 4500 * L * (3197 * 3196 + 2 * 3197) / (r["hidden_ms"] * 1e-3) / 1e12
         rows.append(r)
+    # ... and its fully connected cell (L Q (Q - 1) / 2 lag products per sample and neuron: 1e11 flops per window
+    # at 100 units; timed at 50): passes of 2,304 rows whose launches split the contraction over slices
+    b = dataclasses.replace(synthdata.get_config("paper_fc_q50"), N=4500, Q=3197, d=1, L=50,
+                            w_scale=0.05 * (50 / 3197) ** 0.5)
+    X, T = windows(b)
+    r = timed_fit(b, X, T, "fp32")
+    r["study"] = "long windows"
+    r["stage1_tflops"] = stage1_flops(b) / (r["hidden_ms"] * 1e-3) / 1e12
+    rows.append(r)
     # fit on the first 80 % of the windows, predict the last 20 %
     cfg = synthdata.get_config("cfg3")
     X, T = windows(cfg)

@@ -20,7 +20,7 @@ struct elm_rnn_model {
     elm::FcStepLayout fcs{};      // ELM_CELL_FC_MULTILAG beyond what LDS holds: one launch per step with
     float* dFcW = nullptr;        //   the packed stack [A_{Q-1}; ...; A_1; W; b] and
     float* dFcHist = nullptr;     //   the past states of a chunk of rows (scratch of every hidden-matrix call)
-    float* dFcSums = nullptr;     //   and, for layers of at most 64 units, the carried sums of a block of steps
+    float* dFcSums = nullptr;     //   and sums carried over a block of steps or split over slices of a contraction
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
     void* dWs = nullptr;
@@ -173,8 +173,7 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         if (e == hipSuccess) e = hipMemcpy(mdl->dTiny, tiny.data(), tiny.size() * sizeof(float), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcHist, mdl->fcs.hist_floats * sizeof(float));
-    if (e == hipSuccess && dst == &mdl->dFcW && mdl->fcs.nJB <= 2)
-        e = hipMalloc(&mdl->dFcSums, (size_t)mdl->fcs.chunk_rows * 128 * sizeof(float));
+    if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcSums, mdl->fcs.sums_floats * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);

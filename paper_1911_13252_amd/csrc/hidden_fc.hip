@@ -12,6 +12,7 @@
 // registers); every wave owns a 32-column block of the output and reads its weight fragments straight
 // from L2 in a pre-packed order, eight k-groups ahead.  The history is read once per step ((t-1)*Lk*4
 // bytes per row against 2*(t-1)*Lk*L flops), or once per block of steps for layers of at most 64 units.
+// Passes of few rows (long windows) split each contraction over slices of the operand (gridDim.z).
 //
 // The paper's kernel keeps the history of one (sample, neuron) pair per thread (its H_loc) and so
 // re-reads every other neuron's past outputs from global memory per thread; here a step is one
@@ -55,6 +56,10 @@ struct FcStepArgs {
     unsigned slot_groups;  // k-groups per slot, Lk / 8
     const float* acc_in;   // sums the accumulators start from (row stride ldacc), or null
     int64_t ldacc;
+    // Launches of few rows split the contraction over gridDim.z slices of the operand chunks; slice z
+    // stores its raw sums at out + z * zstride and a second launch adds the slices and applies tanh.
+    int raw;               // 1: raw sums out (the split form)
+    int64_t zstride;
 };
 
 // MS 32-row blocks per wave, CW column blocks per work-group (the other 4/CW waves take further rows);
@@ -63,6 +68,10 @@ struct FcStepArgs {
 template <int MS, int CW, bool EXT>
 __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p) {
     const bool block = EXT && p.block != 0;
+    const bool raw = EXT && (p.block != 0 || p.raw != 0);
+    // this work-group's slice [c0, c1) of the operand chunks
+    const int zs = EXT ? (int)blockIdx.z : 0, nz = EXT ? (int)gridDim.z : 1;
+    const int c0 = (int)((int64_t)p.nchunks * zs / nz), c1 = (int)((int64_t)p.nchunks * (zs + 1) / nz);
     constexpr int WR = 4 / CW, S = 32 * MS * WR, NLD = S / 16;
     extern __shared__ float lds[];             // [2][S][kRS]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -144,12 +153,12 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
 
     floatx4 bq[kPF];
 #pragma unroll
-    for (int u = 0; u < kPF; ++u) bq[u] = buffer_load_x4(wrs, voff, wbase + (unsigned)u * 1024u);
+    for (int u = 0; u < kPF; ++u) bq[u] = buffer_load_x4(wrs, voff, wbase + (unsigned)(c0 * kPF + u) * 1024u);
 
     // the kPF k-groups of chunk c; every weight slot is refilled with the group one chunk ahead (the
     // stack ends in zero groups, so the look-ahead past the last chunk needs no test)
     auto compute = [&](int c) {
-        const float* ap = lds + (c & 1) * S * kRS + (rbase + (lane & 31)) * kRS + (lane >> 5) * 4;
+        const float* ap = lds + ((c - c0) & 1) * S * kRS + (rbase + (lane & 31)) * kRS + (lane >> 5) * 4;
         const unsigned wnext = wbase + (unsigned)(c * kPF + kPF) * 1024u;
         floatx4 a[MS];
 #pragma unroll
@@ -175,35 +184,36 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
     };
 
     const int nfull = p.Kh / kBK;              // chunks that lie inside the history
-    if (nfull > 0) load_history(0); else load_edge(0);
+    if (c0 < nfull) load_history(c0); else load_edge(c0);
     store_chunk(lds);
     __syncthreads();
-    int c = 0;
-    for (; c + 1 < nfull; ++c) {               // chunk c + 1 is fetched while chunk c is contracted
+    int c = c0;
+    for (; c + 1 < nfull && c + 1 < c1; ++c) { // chunk c + 1 is fetched while chunk c is contracted
         load_history(c + 1);
         __builtin_amdgcn_sched_barrier(0);          // the operand loads have the whole chunk to arrive
         compute(c);
-        store_chunk(lds + ((c + 1) & 1) * S * kRS);
+        store_chunk(lds + ((c + 1 - c0) & 1) * S * kRS);
         __syncthreads();
     }
-    for (; c < p.nchunks; ++c) {
-        const bool more = c + 1 < p.nchunks;
+    for (; c < c1; ++c) {
+        const bool more = c + 1 < c1;
         if (more) load_edge(c + 1);
         __builtin_amdgcn_sched_barrier(0);
         compute(c);
-        if (more) store_chunk(lds + ((c + 1) & 1) * S * kRS);
+        if (more) store_chunk(lds + ((c + 1 - c0) & 1) * S * kRS);
         __syncthreads();
     }
 
     if (!active) return;
     const int col = jb * 32 + (lane & 31);
-    if (block) {                               // raw sums of step jstep of the block, all 32 columns of the block
+    if (raw) {                                 // raw sums (of step jstep of a block), all 32 columns of the block
+        float* o = p.out + (int64_t)zs * p.zstride + jstep * 32 * p.nJB + col;
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int64_t row = row0 + rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                if (row < p.rows) p.out[row * p.ldo + jstep * 32 * p.nJB + col] = acc[ms][i];
+                if (row < p.rows) o[row * p.ldo] = acc[ms][i];
             }
         return;
     }
@@ -218,8 +228,20 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
         }
 }
 
+// h = tanh(sum of the nz slices' raw sums), zeros in the padding columns; the slices are added in order
+__global__ __launch_bounds__(256) void fc_reduce_kernel(const float* __restrict__ part, int nz, int64_t zstride,
+                                                        int ldp, int rows, int L, int ncols,
+                                                        float* __restrict__ out, int64_t ldo) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)rows * ncols) return;
+    const int row = (int)(idx / ncols), col = (int)(idx - (int64_t)row * ncols);
+    float s = 0.0f;
+    for (int z = 0; z < nz; ++z) s += part[z * zstride + (int64_t)row * ldp + col];
+    out[row * ldo + col] = col < L ? tanh_f(s) : 0.0f;
+}
+
 template <int MS, int CW, bool EXT = false>
-hipError_t launch_step(const FcStepArgs& a, int ycount, hipStream_t stream) {
+hipError_t launch_step(const FcStepArgs& a, int ycount, hipStream_t stream, int slices = 1) {
     constexpr int S = 32 * MS * (4 / CW);
     constexpr size_t lds = (size_t)2 * S * kRS * sizeof(float);
     auto kern = fc_step_kernel<MS, CW, EXT>;
@@ -229,7 +251,8 @@ hipError_t launch_step(const FcStepArgs& a, int ycount, hipStream_t stream) {
         if (e != hipSuccess) return e;
     }
     const unsigned tiles = (unsigned)((a.rows + S - 1) / S);
-    hipLaunchKernelGGL(kern, dim3(tiles, (unsigned)ycount), dim3(kThreads), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3(tiles, (unsigned)ycount, (unsigned)(EXT ? slices : 1)), dim3(kThreads), lds,
+                       stream, a);
     return hipGetLastError();
 }
 
@@ -257,6 +280,13 @@ bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
     // slower (100,096 rows: three rounds and a fraction), and so did 49,152 (one and a half)
     lay.chunk_rows = rows < 256 ? 256 : rows > 65536 ? 65536 : rows;
     lay.hist_floats = (size_t)lay.chunk_rows * lay.ring * lay.Lk;
+    // scratch sums: a block of steps carried for layers of at most 64 units ([row][128]); eight slices of raw
+    // sums for launches of fewer than 128 work-groups ([slice][row][32 nJB])
+    const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
+    const int64_t few_rows = (int64_t)128 * 32 * (4 / cw) < lay.chunk_rows ? (int64_t)128 * 32 * (4 / cw) : lay.chunk_rows;
+    const size_t carried = lay.nJB <= 2 ? (size_t)lay.chunk_rows * 128 : 0;
+    const size_t split = (size_t)8 * few_rows * 32 * lay.nJB;
+    lay.sums_floats = carried > split ? carried : split;
     if (out != nullptr) *out = lay;
     return true;
 }
@@ -294,9 +324,9 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
     if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
     const int ycount = (lay.nJB + cw - 1) / cw;
-    // steps per block: the waves that a layer of one or two column blocks leaves free take further steps
-    const int B = (sums != nullptr && lay.nJB <= 2) ? 4 / lay.nJB : 1;
-    const int ldsums = 128;                    // [row][B][32 nJB]
+    const int ldsums = 128;                    // carried sums of a block of steps: [row][B][32 nJB]
+    const int ldp = 32 * lay.nJB;              // raw sums of a split launch: [slice][row][32 nJB]
+    const int S1 = 32 * (4 / cw);              // rows of the smallest tile
     // passes of equal size (a multiple of 256 rows) rather than full buffers and a short last one
     const int64_t passes = (N + lay.chunk_rows - 1) / lay.chunk_rows;
     const int64_t per_pass = ((N + passes - 1) / passes + 255) / 256 * 256;
@@ -309,6 +339,12 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
         base.jb_stride = (unsigned)lay.KGpad * 1024u;
         base.d = lay.d; base.L = lay.L; base.nJB = lay.nJB; base.rows = (int)rows;
         base.nsteps = 1; base.ldacc = ldsums;
+        // a pass of few rows (long windows: the history of 1,000 rows can be 1 GB) leaves compute units idle:
+        // its launches split the contraction over up to 8 slices of the operand chunks instead
+        const int64_t wgs = (rows + S1 - 1) / S1 * ycount;
+        const bool few = sums != nullptr && wgs < 128 && (size_t)8 * rows * ldp <= lay.sums_floats;
+        // steps per block: the waves that a layer of one or two column blocks leaves free take further steps
+        const int B = (sums != nullptr && lay.nJB <= 2 && !few) ? 4 / lay.nJB : 1;
         for (int t0 = 0; t0 < Q_run; t0 += B) {
             const int nb = Q_run - t0 < B ? Q_run - t0 : B;
             const bool carried = B > 1 && t0 > 0;
@@ -343,6 +379,26 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
                     a.out = H + r0 * lay.L; a.ldo = lay.L; a.ncols = lay.L;
                 } else {
                     a.out = hist + (int64_t)(t - 1) * slot_floats; a.ldo = lay.Lk; a.ncols = lay.Lk;
+                }
+                int slices = 1;
+                if (few) {
+                    slices = (int)(256 / wgs) < 8 ? (int)(256 / wgs) : 8;
+                    if (slices > a.nchunks / 4) slices = a.nchunks / 4;      // at least four chunks per slice
+                }
+                if (slices >= 2) {
+                    float* out = a.out;
+                    const int64_t ldo = a.ldo;
+                    a.raw = 1; a.out = sums; a.ldo = ldp; a.zstride = rows * ldp;
+                    hipError_t e = cw == 4   ? launch_step<1, 4, true>(a, ycount, stream, slices)
+                                   : cw == 2 ? launch_step<1, 2, true>(a, ycount, stream, slices)
+                                             : launch_step<1, 1, true>(a, ycount, stream, slices);
+                    if (e != hipSuccess) return e;
+                    const int64_t total = rows * a.ncols;
+                    hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                                       sums, slices, a.zstride, ldp, (int)rows, lay.L, a.ncols, out, ldo);
+                    e = hipGetLastError();
+                    if (e != hipSuccess) return e;
+                    continue;
                 }
                 // 64-row blocks per wave while they still give every compute unit two work-groups
                 const bool big = cw > 1 && (rows + 64 * (4 / cw) - 1) / (64 * (4 / cw)) >= 512;

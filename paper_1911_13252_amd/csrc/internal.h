@@ -43,11 +43,12 @@ struct FcStepLayout {
     size_t floats;        // packed stack: nJB * KGpad * 256
     int64_t chunk_rows;   // rows the history buffer holds (a multiple of 256, at most 65,536)
     size_t hist_floats;   // chunk_rows * ring * Lk
+    size_t sums_floats;   // scratch for carried and split sums
 };
 // false: the shape is out of range (stack of 4 GiB or more, or a history row of 8 MiB or more)
 bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
 void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
-// sums: chunk_rows x 128 floats of scratch for layers of at most 64 units (steps taken in blocks), else null
+// hist: lay.hist_floats, sums: lay.sums_floats of model-owned scratch
 hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, float* sums,
                                   const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream);

@@ -59,3 +59,26 @@ def test_paper_elman_on_its_longest_window_shape(elm):
     assert h_close(H[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
     assert torch.isfinite(H).all()
     model.close()
+
+
+def test_fully_connected_cell_on_the_longest_window_shape(elm):
+    """4,500 windows of 3,197 steps, 50 units: a window's history is 716 KB, a pass holds 2,304 rows and
+    its launches split the contraction over slices of the operand; 5.1 million lag products per window,
+    so the oracle takes three rows."""
+    N, Q, d, L = 4500, 3197, 1, 50
+    rng = np.random.default_rng(41)
+    W = rng.uniform(-1, 1, (d, L)).astype(np.float32)
+    a = 0.7 / np.sqrt(L * (Q - 1))
+    A = rng.uniform(-a, a, (Q, L, L)).astype(np.float32)
+    A[:40] *= 8.0                                            # recent lags dominate, all count
+    b = rng.uniform(-0.5, 0.5, L).astype(np.float32)
+    series = synthdata.make_series(N + Q, d, 78, 0.05).astype(np.float32)
+    dev, X = sliding(series, N, Q, d)
+    model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
+    H = elm.hidden(model, X)
+    rows = np.array([0, 2303, 2304, 4499])                   # both sides of the pass edge
+    Xs = np.lib.stride_tricks.sliding_window_view(series, (Q, d))[rows, 0]
+    ref = ocells.hidden_fc_multilag(Xs, W, A, b)
+    assert h_close(H[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
+    assert torch.isfinite(H).all()
+    model.close()
