@@ -420,7 +420,7 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
                 size_t workspace_bytes, void* hip_stream, float* H_out, float* beta_out,
                 double* beta64_out, elm_rnn_stats* stats, elm_rnn_model** model_out) {
     if (X == nullptr || T == nullptr || beta_out == nullptr || model_out == nullptr) return ELM_EINVAL;
-    if (N < 1 || N < L) return ELM_EINVAL;
+    if (N < 1 || N < L || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
     const size_t need = elm_rnn_fit_workspace_bytes(N, L, m, H_out == nullptr);
