@@ -19,6 +19,7 @@ struct elm_rnn_model {
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
     elm::FcStepLayout fcs{};      // ELM_CELL_FC_MULTILAG beyond what LDS holds: one launch per step with
     float* dFcW = nullptr;        //   the packed stack [A_{Q-1}; ...; A_1; W; b] and
+    float* dFcW16 = nullptr;      //   the same stack per 16-column unit (layers of 65 to 96 units)
     float* dFcHist = nullptr;     //   the past states of a chunk of rows (scratch of every hidden-matrix call)
     float* dFcSums = nullptr;     //   and sums carried over a block of steps or split over slices of a contraction
     int contraction = ELM_CONTRACT_FP32;
@@ -174,6 +175,13 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
     }
     if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcHist, mdl->fcs.hist_floats * sizeof(float));
     if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcSums, mdl->fcs.sums_floats * sizeof(float));
+    if (e == hipSuccess && dst == &mdl->dFcW && mdl->fcs.NU > 0) {
+        std::vector<float> units(mdl->fcs.floats16);
+        pack_weights_fc_rows(mdl->fcs, mdl->W.data(), mdl->U.data(), mdl->b.data(), units.data());
+        e = hipMalloc(&mdl->dFcW16, units.size() * sizeof(float));
+        if (e == hipSuccess)
+            e = hipMemcpy(mdl->dFcW16, units.data(), units.size() * sizeof(float), hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
@@ -212,7 +220,7 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
                                   stream);
     }
     if (mdl->dFcW != nullptr)
-        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcHist, mdl->dFcSums, X, ldx_n, ldx_q, N, Q_run, H,
+        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcW16, mdl->dFcHist, mdl->dFcSums, X, ldx_n, ldx_q, N, Q_run, H,
                                       stream);
     if (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dTiny != nullptr)
         return launch_hidden_tiny(mdl->cell, mdl->d, mdl->L, mdl->dTiny, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
@@ -377,6 +385,7 @@ void elm_rnn_free(elm_rnn_model* model) {
     if (model->dTiny) (void)hipFree(model->dTiny);
     if (model->dDiag) (void)hipFree(model->dDiag);
     if (model->dFcW) (void)hipFree(model->dFcW);
+    if (model->dFcW16) (void)hipFree(model->dFcW16);
     if (model->dFcHist) (void)hipFree(model->dFcHist);
     if (model->dFcSums) (void)hipFree(model->dFcSums);
     if (model->dWs) (void)hipFree(model->dWs);

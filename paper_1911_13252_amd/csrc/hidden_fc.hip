@@ -60,7 +60,80 @@ struct FcStepArgs {
     // stores its raw sums at out + z * zstride and a second launch adds the slices and applies tanh.
     int raw;               // 1: raw sums out (the split form)
     int64_t zstride;
+    // fc_rows_kernel: the stack packed per 16-column unit; the kernel runs the steps t_first .. t_last of a pass
+    // itself (a tile's rows depend on no other tile) and derives Kh, kg0, nchunks, X and out per step
+    const float* Wp16;
+    unsigned wp16_bytes;
+    int t_first, t_last, Q_run, ring;
+    int64_t ldx_q;         // X: x_1 of the pass's first row
+    float* hist_out;       // = hist (written)
+    float* H;              // the pass's rows of H (row stride L)
 };
+
+// ---- the operand [h(1) | ... | h(t-1) | x_t | 1 | 0 ...] of a tile, streamed in chunks of kBK columns.
+// A thread moves NLD 16-byte pieces per chunk: row (tid>>4) + 16*q of the tile, columns 4*(tid&15) .. +3.
+
+// byte offset of the thread's rows inside a slot; rows past the end get an offset that is out of range
+template <int NLD>
+__device__ __forceinline__ void operand_row_offsets(unsigned (&hoff)[NLD], const FcStepArgs& p, int64_t row0, int lr) {
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int64_t row = row0 + lr + 16 * q;
+        hoff[q] = row < p.rows ? (unsigned)(row * p.Lk * 4) : 0xFFFFFFF0u;
+    }
+}
+
+// operand column k lies in slot k / Lk; Lk and k are multiples of 4, so a piece stays inside a slot
+__device__ __forceinline__ unsigned operand_slot_offset(const FcStepArgs& p, int k) {
+    const int sl = k / p.Lk;
+    return ((unsigned)sl * p.slot_floats + (unsigned)(k - sl * p.Lk)) * 4u;
+}
+
+// a chunk that lies inside the history: range-checked loads, rows past the end read as zero
+template <int NLD>
+__device__ __forceinline__ void operand_load_history(floatx4 (&stage)[NLD], const unsigned (&hoff)[NLD],
+                                                     __amdgpu_buffer_rsrc_t hrs, unsigned so) {
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const unsigned off = hoff[q] == 0xFFFFFFF0u ? hoff[q] : hoff[q] + so;
+        stage[q] = buffer_load_x4(hrs, off, 0);
+    }
+}
+
+// the same with the offsets rebuilt from the first piece's (rows 16 apart): eight fewer live registers
+template <int NLD>
+__device__ __forceinline__ void operand_load_history_strided(floatx4 (&stage)[NLD], unsigned hoff0, unsigned step,
+                                                             int valid, __amdgpu_buffer_rsrc_t hrs, unsigned so) {
+#pragma unroll
+    for (int q = 0; q < NLD; ++q)      // pieces q >= valid belong to rows past the end: out of range, read as zero
+        stage[q] = buffer_load_x4(hrs, q < valid ? hoff0 + (unsigned)q * step + so : 0xFFFFFFF0u, 0);
+}
+
+// a chunk that holds the end of the history, x_t, the constant 1 and the zero padding (no input columns
+// when the launch only pre-sums finished slots)
+template <int NLD>
+__device__ __forceinline__ void operand_load_edge(floatx4 (&stage)[NLD], const unsigned (&hoff)[NLD],
+                                                  __amdgpu_buffer_rsrc_t hrs, const FcStepArgs& p, int Kh,
+                                                  const float* X, int64_t row0, int lr, int k, bool with_input) {
+    const unsigned so = k < Kh ? operand_slot_offset(p, k) : 0u;
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int64_t row = row0 + lr + 16 * q;
+        floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < p.rows) {
+            if (k < Kh) {                  // Kh and k are multiples of 4: a piece never straddles the edge
+                v = buffer_load_x4(hrs, hoff[q] + so, 0);
+            } else if (with_input) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int kk = k + e - Kh;
+                    v[e] = kk < p.d ? X[row * p.ldx_n + kk] : (kk == p.d ? 1.0f : 0.0f);
+                }
+            }
+        }
+        stage[q] = v;
+    }
+}
 
 // MS 32-row blocks per wave, CW column blocks per work-group (the other 4/CW waves take further rows);
 // EXT: the launch may be a block launch or start from carried sums (layers of at most 64 units only: the
@@ -92,48 +165,14 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
     const int lr = tid >> 4, lk = (tid & 15) * 4;
     const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(p.hist), 0, (int)p.hist_bytes, 0x00020000);
-    unsigned hoff[NLD];                        // byte offset of the piece's row inside a slot; rows past the end: out of range
-#pragma unroll
-    for (int q = 0; q < NLD; ++q) {
-        const int64_t row = row0 + lr + 16 * q;
-        hoff[q] = row < p.rows ? (unsigned)(row * p.Lk * 4) : 0xFFFFFFF0u;
-    }
-    // operand column k lies in slot k / Lk; Lk and k are multiples of 4, so a piece stays inside a slot
-    auto slot_offset = [&](int k) {
-        const int sl = k / p.Lk;
-        return ((unsigned)sl * p.slot_floats + (unsigned)(k - sl * p.Lk)) * 4u;
-    };
+    unsigned hoff[NLD];
+    operand_row_offsets<NLD>(hoff, p, row0, lr);
     floatx4 stage[NLD];
-    // a chunk that lies inside the history: range-checked loads, rows past the end read as zero
     auto load_history = [&](int c) {
-        const unsigned so = slot_offset(c * kBK + lk);
-#pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const unsigned off = hoff[q] == 0xFFFFFFF0u ? hoff[q] : hoff[q] + so;
-            stage[q] = buffer_load_x4(hrs, off, 0);
-        }
+        operand_load_history<NLD>(stage, hoff, hrs, operand_slot_offset(p, c * kBK + lk));
     };
-    // a chunk that holds the end of the history, x_t, the constant 1 and the zero padding
     auto load_edge = [&](int c) {
-        const int k = c * kBK + lk;
-        const unsigned so = k < p.Kh ? slot_offset(k) : 0u;
-#pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const int64_t row = row0 + lr + 16 * q;
-            floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (row < p.rows) {
-                if (k < p.Kh) {            // Kh and k are multiples of 4: a piece never straddles the edge
-                    v = buffer_load_x4(hrs, hoff[q] + so, 0);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int kk = k + e - p.Kh;
-                        if (!block) v[e] = kk < p.d ? p.X[row * p.ldx_n + kk] : (kk == p.d ? 1.0f : 0.0f);
-                    }
-                }
-            }
-            stage[q] = v;
-        }
+        operand_load_edge<NLD>(stage, hoff, hrs, p, p.Kh, p.X, row0, lr, c * kBK + lk, !block);
     };
     auto store_chunk = [&](float* buf) {
 #pragma unroll
@@ -228,6 +267,168 @@ __global__ __launch_bounds__(kThreads, 2) void fc_step_kernel(const FcStepArgs p
         }
 }
 
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ floatx2 buffer_load_x2(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff) {
+    typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+    const uintx2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, soff, 0);
+    return __builtin_bit_cast(floatx2, v);
+}
+
+// Layers of 65 to 96 units: three 32-column blocks would leave one wave in four idle.  Here the four
+// waves split the rows of a 128-row tile instead and every wave contracts all NU = ceil(L / 16) column
+// units for its 32 rows with the 16x16x4 matrix instruction: no idle wave, 16-column granularity.  The
+// kernel also runs all steps of a pass itself (a tile's rows depend on no other tile), with a
+// work-group-scope fence and a barrier between steps.  Lane (r = lane % 16, q = lane / 16) of an A fragment holds row r, columns
+// 8g + 2q + e of k-group g; of a B fragment stack rows 8g + 2q + e, column r of the unit (e = 0, 1: one
+// 8-byte load each); accumulator register v of a lane is row 4q + v, column r of the 16 x 16 tile.
+// Four k-groups of weight fragments are in flight; the operand loads of the next chunk are issued in
+// the middle of a chunk, after the refills this chunk still waits for and before those of the next one,
+// so no wait for a weight fragment ever waits for an operand load.
+template <int NU>
+__global__ __launch_bounds__(kThreads, 2) void fc_rows_kernel(const FcStepArgs args) {
+    constexpr int S = 128, NLD = S / 16, PF = 4;
+    extern __shared__ float lds[];             // [2][S][kRS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rbase = wave * 32;
+    const int64_t row0 = (int64_t)blockIdx.x * S;
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(args.Wp16), 0, (int)args.wp16_bytes, 0x00020000);
+    const unsigned voff = (unsigned)lane * 8u;
+    const int lr = tid >> 4, lk = (tid & 15) * 4;
+    const __amdgpu_buffer_rsrc_t hrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(args.hist), 0, (int)args.hist_bytes, 0x00020000);
+    // rows of this thread's pieces: row0 + lr + 16 q; `valid` of them exist
+    const unsigned hoff0 = (unsigned)((row0 + lr) * args.Lk * 4), hstep = (unsigned)(16 * args.Lk * 4);
+    const int64_t left = args.rows - (row0 + lr);
+    const int valid = left <= 0 ? 0 : (int)((left + 15) / 16 < NLD ? (left + 15) / 16 : NLD);
+
+    for (int t = args.t_first; t <= args.t_last; ++t) {
+        // this step's view of the operand and its weights
+        const int Kh = (t - 1) * args.Lk;
+        const unsigned kg0 = (unsigned)((args.ring - (t - 1)) * (int)args.slot_groups);
+        const int nchunks = ((Kh + args.d + 1 + 7) / 8 + 7) / 8;
+        const float* Xt = args.X + (int64_t)(t - 1) * args.ldx_q;
+        const bool last = t == args.Q_run;
+        float* out = last ? args.H : args.hist_out + (int64_t)(t - 1) * args.slot_floats;
+        const int64_t ldo = last ? args.L : args.Lk;
+        const int ncols = last ? args.L : args.Lk;
+        const unsigned wbase = kg0 * (NU * 512u);      // fragments: [k-group][unit][lane][2], 512 bytes each
+
+        floatx4 stage[NLD];
+        const int nfull = Kh / kBK;            // chunks that lie inside the history
+        auto load_history = [&](int c) {
+            operand_load_history_strided<NLD>(stage, hoff0, hstep, valid, hrs,
+                                              operand_slot_offset(args, c * kBK + lk));
+        };
+        auto load_edge = [&](int c) {
+            unsigned hoff[NLD];
+#pragma unroll
+            for (int q = 0; q < NLD; ++q) hoff[q] = hoff0 + (unsigned)q * hstep;     // used for existing rows only
+            operand_load_edge<NLD>(stage, hoff, hrs, args, Kh, Xt, row0, lr, c * kBK + lk, true);
+        };
+        auto store_chunk = [&](float* buf) {
+#pragma unroll
+            for (int q = 0; q < NLD; ++q)
+                *reinterpret_cast<floatx4*>(buf + (lr + 16 * q) * kRS + lk) = stage[q];
+        };
+
+        floatx4 acc[2][NU];
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int cu = 0; cu < NU; ++cu) acc[r][cu] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        floatx2 bq[PF][NU];
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+#pragma unroll
+            for (int cu = 0; cu < NU; ++cu)
+                bq[u][cu] = buffer_load_x2(wrs, voff + (unsigned)cu * 512u, wbase + (unsigned)u * (NU * 512u));
+
+        // k-groups 4h .. 4h+3 of chunk c; slot u is refilled with the group four ahead
+        auto half = [&](int c, int h) {
+            const float* ap = lds + (c & 1) * S * kRS + (rbase + (lane & 15)) * kRS + (lane >> 4) * 2 + h * 32;
+            const unsigned wnext = wbase + (unsigned)(c * 8 + h * 4 + PF) * (NU * 512u);
+            floatx2 a0 = *reinterpret_cast<const floatx2*>(ap), a1 = *reinterpret_cast<const floatx2*>(ap + 16 * kRS);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int un = u + 1 < 4 ? u + 1 : u;
+                const floatx2 n0 = *reinterpret_cast<const floatx2*>(ap + un * 8);
+                const floatx2 n1 = *reinterpret_cast<const floatx2*>(ap + 16 * kRS + un * 8);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int cu = 0; cu < NU; ++cu) {
+                        acc[0][cu] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[e], bq[u][cu][e], acc[0][cu], 0, 0, 0);
+                        acc[1][cu] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[e], bq[u][cu][e], acc[1][cu], 0, 0, 0);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int cu = 0; cu < NU; ++cu)
+                    bq[u][cu] = buffer_load_x2(wrs, voff + (unsigned)cu * 512u, wnext + (unsigned)u * (NU * 512u));
+                a0 = n0;
+                a1 = n1;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
+        if (nfull > 0) load_history(0); else load_edge(0);
+        store_chunk(lds);
+        __syncthreads();
+        int c = 0;
+        for (; c + 1 < nfull; ++c) {           // branch-free body: the waits for weight fragments stay exact
+            half(c, 0);
+            load_history(c + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            half(c, 1);
+            store_chunk(lds + ((c + 1) & 1) * S * kRS);
+            __syncthreads();
+        }
+        for (; c < nchunks; ++c) {
+            const bool more = c + 1 < nchunks;
+            half(c, 0);
+            if (more) load_edge(c + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            half(c, 1);
+            if (more) store_chunk(lds + ((c + 1) & 1) * S * kRS);
+            __syncthreads();
+        }
+
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int cu = 0; cu < NU; ++cu) {
+                const int col = 16 * cu + (lane & 15);
+                if (col >= ncols) continue;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t row = row0 + rbase + 16 * r + 4 * (lane >> 4) + v;
+                    if (row < args.rows) out[row * ldo + col] = col < args.L ? tanh_f(acc[r][cu][v]) : 0.0f;
+                }
+            }
+        // the next step reads the slot this one wrote: the tile's rows are this work-group's alone (tiles of
+        // 128 rows are whole cache lines of a slot), so a fence of work-group scope is enough (a device-scope
+        // one writes back and invalidates the whole L2 of the die: measured 213 ms against 176 ms per fit)
+        if (t < args.t_last) {
+            __threadfence_block();
+            __syncthreads();
+        }
+    }
+}
+
+template <int NU>
+hipError_t launch_rows(const FcStepArgs& a, hipStream_t stream) {
+    constexpr size_t lds = (size_t)2 * 128 * kRS * sizeof(float);
+    auto kern = fc_rows_kernel<NU>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((a.rows + 127) / 128)), dim3(kThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
 // h = tanh(sum of the nz slices' raw sums), zeros in the padding columns; the slices are added in order
 __global__ __launch_bounds__(256) void fc_reduce_kernel(const float* __restrict__ part, int nz, int64_t zstride,
                                                         int ldp, int rows, int L, int ncols,
@@ -280,6 +481,10 @@ bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
     // slower (100,096 rows: three rounds and a fraction), and so did 49,152 (one and a half)
     lay.chunk_rows = rows < 256 ? 256 : rows > 65536 ? 65536 : rows;
     lay.hist_floats = (size_t)lay.chunk_rows * lay.ring * lay.Lk;
+    // 97 to 112 units would take 7 units: measured 1.6 % faster than four 32-column blocks, with 22 registers
+    // spilled; those layers keep the 32-column kernel
+    lay.NU = (L > 64 && L <= 96) ? (L + 15) / 16 : 0;
+    lay.floats16 = (size_t)lay.NU * KGpad * 128;
     // scratch sums: a block of steps carried for layers of at most 64 units ([row][128]); eight slices of raw
     // sums for launches of fewer than 128 work-groups ([slice][row][32 nJB])
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
@@ -318,8 +523,33 @@ void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float*
                 }
 }
 
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, float* sums,
-                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+// The same stack per 16-column unit: [k-group][unit][lane][e], row = 8*group + 2*(lane>>4) + e, column = lane&15.
+void pack_weights_fc_rows(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out) {
+    const int L = lay.L, d = lay.d, Lk = lay.Lk;
+    const int64_t hist_rows = (int64_t)lay.ring * Lk;
+    for (size_t i = 0; i < lay.floats16; ++i) out[i] = 0.0f;
+    for (int cu = 0; cu < lay.NU; ++cu)
+        for (int kg = 0; kg < lay.KGtot; ++kg)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 2; ++e) {
+                    const int64_t k = (int64_t)kg * 8 + (lane >> 4) * 2 + e;
+                    const int j = cu * 16 + (lane & 15);
+                    if (j >= L) continue;
+                    float v = 0.0f;
+                    if (k < hist_rows) {
+                        const int s = (int)(k / Lk), mm = (int)(k - (int64_t)s * Lk);
+                        if (mm < L) v = A[((size_t)(lay.ring - s - 1) * L + mm) * L + j];
+                    } else if (k - hist_rows < d) {
+                        v = W[(size_t)(k - hist_rows) * L + j];
+                    } else if (k - hist_rows == d) {
+                        v = b[j];
+                    }
+                    out[(((size_t)kg * lay.NU + cu) * 64 + lane) * 2 + e] = v;
+                }
+}
+
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, float* hist,
+                                  float* sums, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream) {
     if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
@@ -339,12 +569,25 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, floa
         base.jb_stride = (unsigned)lay.KGpad * 1024u;
         base.d = lay.d; base.L = lay.L; base.nJB = lay.nJB; base.rows = (int)rows;
         base.nsteps = 1; base.ldacc = ldsums;
+        base.Wp16 = Wp16; base.wp16_bytes = (unsigned)(lay.floats16 * sizeof(float));
+
         // a pass of few rows (long windows: the history of 1,000 rows can be 1 GB) leaves compute units idle:
         // its launches split the contraction over up to 8 slices of the operand chunks instead
         const int64_t wgs = (rows + S1 - 1) / S1 * ycount;
         const bool few = sums != nullptr && wgs < 128 && (size_t)8 * rows * ldp <= lay.sums_floats;
         // steps per block: the waves that a layer of one or two column blocks leaves free take further steps
         const int B = (sums != nullptr && lay.nJB <= 2 && !few) ? 4 / lay.nJB : 1;
+        if (Wp16 != nullptr && lay.NU > 0 && (rows + 127) / 128 >= 256) {       // every compute unit gets a tile
+            FcStepArgs a = base;
+            a.hist = hist; a.hist_out = hist;
+            a.hist_bytes = (unsigned)(lay.ring * slot_floats * (int64_t)sizeof(float));
+            a.X = X + r0 * ldx_n; a.ldx_q = ldx_q;
+            a.H = H + r0 * lay.L;
+            a.t_first = 1; a.t_last = Q_run; a.Q_run = Q_run; a.ring = lay.ring;
+            const hipError_t e = lay.NU == 5 ? launch_rows<5>(a, stream) : launch_rows<6>(a, stream);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         for (int t0 = 0; t0 < Q_run; t0 += B) {
             const int nb = Q_run - t0 < B ? Q_run - t0 : B;
             const bool carried = B > 1 && t0 > 0;

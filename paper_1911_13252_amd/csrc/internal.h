@@ -44,13 +44,17 @@ struct FcStepLayout {
     int64_t chunk_rows;   // rows the history buffer holds (a multiple of 256, at most 65,536)
     size_t hist_floats;   // chunk_rows * ring * Lk
     size_t sums_floats;   // scratch for carried and split sums
+    int NU;               // 16-column units of the row-split kernel (layers of 65 to 96 units), else 0
+    size_t floats16;      // the stack packed per unit: NU * KGpad * 128
 };
 // false: the shape is out of range (stack of 4 GiB or more, or a history row of 8 MiB or more)
 bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
 void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
+void pack_weights_fc_rows(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
 // hist: lay.hist_floats, sums: lay.sums_floats of model-owned scratch
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, float* hist, float* sums,
-                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+// Wp16: the per-unit packing (lay.floats16) where lay.NU > 0, else null
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, float* hist,
+                                  float* sums, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream);
 
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,

@@ -73,22 +73,29 @@ def pass_rows(N, Q, L):
 
 # Launches large enough for 64-row blocks per wave, and more rows than the history buffer holds (the rows
 # are then taken in equal passes over the steps); rows are independent, so the oracle is evaluated on
-# samples: the first and last rows, those around the pass boundary and random ones
+# samples: the first and last rows, those around the pass boundary and random ones.  Layers of 65 to 96
+# units with at least 256 tiles of 128 rows take the kernel whose waves split the rows (5 or 6 column
+# units of 16) and that runs all steps of a pass in one launch; wider layers take the 32-column blocks.
 @pytest.mark.parametrize("N,Q,d,L,ns", [(131_000, 21, 1, 64, 200), (40_000, 14, 2, 100, 200), (50_001, 15, 1, 97, 200),
+                                        (33_000, 20, 1, 70, 200), (33_011, 16, 3, 90, 200), (34_000, 12, 1, 120, 200),
+                                        (140_000, 19, 2, 72, 150),
                                         (66_000, 160, 1, 8, 150), (60_000, 100, 1, 100, 40)])
 def test_hidden_per_step_path_many_rows(elm, N, Q, d, L, ns):
     W, A, b = weights(Q, d, L, seed=Q + L)
     X = np.random.default_rng(Q).uniform(-1, 1, (N, Q, d)).astype(np.float32)
     model = elm.Model.from_weights("fc_multilag", Q, 1, W, A, b)
-    H = elm.hidden(model, torch.from_numpy(X).cuda()).cpu().numpy()
+    Xd = torch.from_numpy(X).cuda()
+    H = elm.hidden(model, Xd).cpu().numpy()
+    Hhalf = elm.hidden(model, Xd, Q_run=Q // 2).cpu().numpy()
     model.close()
     edge = pass_rows(N, Q, L)
-    if (N, Q, L) in ((131_000, 21, 64), (66_000, 160, 8), (60_000, 100, 100)):
-        assert edge < N                              # these two cases take two passes
+    if (N, Q, L) in ((131_000, 21, 64), (66_000, 160, 8), (60_000, 100, 100), (140_000, 19, 72)):
+        assert edge < N                              # these cases take two or three passes
     idx = np.unique(np.concatenate([np.arange(0, ns), np.arange(N - ns, N),
                                     np.clip(np.arange(edge - ns, edge + ns), 0, N - 1),
                                     np.random.default_rng(1).integers(0, N, ns)]))
     assert h_close(H[idx], ocells.hidden_fc_multilag(X[idx], W, A, b))
+    assert h_close(Hhalf[idx], ocells.hidden_fc_multilag(X[idx], W, A, b, steps=Q // 2))
     assert np.all(np.isfinite(H)) and np.abs(H).max() <= 1.0
 
 
