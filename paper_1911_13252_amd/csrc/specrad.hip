@@ -14,42 +14,43 @@
 namespace elm {
 namespace {
 
-constexpr int TS = 32;
-constexpr int KC = 128;     // contraction indices staged in LDS at a time
+constexpr int TS = 32;      // a work-group owns a 32 x 32 tile of the square, a wave a 16 x 16 quarter of it
+
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 // out = (M / ||M||_F)^2 with ||M||_F^2 = the sum of partial_prev[0 .. nprev) (summed in index order by
 // every work-group, so all of them scale by the same value); partial[block] = sum of squares of the
 // block's entries of out; work-group (0, 0) also stores ||M||_F in norm_slot[0].
+// The product runs on the float64 matrix instruction (16 x 16 x 4): lane (r = lane % 16, q = lane / 16)
+// supplies M[row0 + r][4s + q] and M[4s + q][col0 + r] for k-step s and holds rows 4q .. 4q+3, column r of
+// the 16 x 16 result.  Operands come straight from L2 (a 100 x 100 matrix is 80 KB), eight k-steps of
+// loads in flight: a squaring of the chain of 48 is then little more than a launch and one round of loads.
 __global__ __launch_bounds__(256) void square_kernel(const double* __restrict__ M, double* __restrict__ out,
                                                      int n, const double* __restrict__ partial_prev, int nprev,
                                                      double* __restrict__ partial, double* __restrict__ norm_slot) {
-    // the row panel and the column panel of this tile, KC contraction indices at a time (all of them for
-    // n <= 128: one round of loads and one barrier per squaring, which is what a chain of 48 dependent
-    // 100 x 100 squarings is made of)
-    __shared__ double As[TS][KC + 1], Bs[KC][TS + 1];
-    __shared__ double red[256];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;      // a thread owns a 2 x 2 patch
-    const int row0 = blockIdx.y * TS, col0 = blockIdx.x * TS;
-    double acc[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
-    for (int k0 = 0; k0 < n; k0 += KC) {
-        const int kc = min(KC, n - k0);
-        for (int e = tid; e < TS * KC; e += 256) {
-            const int r = e / KC, c = e - r * KC;                   // As: row r, contraction index c
-            As[r][c] = (row0 + r < n && c < kc) ? M[(size_t)(row0 + r) * n + k0 + c] : 0.0;
-            const int kr = e / TS, cc = e - kr * TS;                // Bs: contraction index kr, column cc
-            Bs[kr][cc] = (kr < kc && col0 + cc < n) ? M[(size_t)(k0 + kr) * n + col0 + cc] : 0.0;
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int row0 = blockIdx.y * TS + (wave >> 1) * 16, col0 = blockIdx.x * TS + (wave & 1) * 16;
+    const bool row_ok = row0 + r < n, col_ok = col0 + r < n;
+    const double* arow = M + (size_t)(row0 + r) * n;        // read only where row_ok
+    const double* bcol = M + col0 + r;                      // read only where col_ok
+    doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+    constexpr int U = 8;                                    // k-steps per batch of loads
+    const int steps = (n + 3) / 4;
+    double a[U], b[U];
+    auto fetch = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = 4 * (s0 + u) + q;
+            a[u] = (row_ok && k < n) ? arow[k] : 0.0;
+            b[u] = (col_ok && k < n) ? bcol[(size_t)k * n] : 0.0;
         }
-        __syncthreads();
-#pragma unroll 8
-        for (int k = 0; k < kc; ++k) {
-            const double a0 = As[2 * ty][k], a1 = As[2 * ty + 1][k];
-            const double b0 = Bs[k][2 * tx], b1 = Bs[k][2 * tx + 1];
-            acc[0][0] = fma(a0, b0, acc[0][0]);
-            acc[0][1] = fma(a0, b1, acc[0][1]);
-            acc[1][0] = fma(a1, b0, acc[1][0]);
-            acc[1][1] = fma(a1, b1, acc[1][1]);
-        }
-        __syncthreads();
+    };
+    for (int s0 = 0; s0 < steps; s0 += U) {
+        fetch(s0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[u], acc, 0, 0, 0);
     }
     double s2 = 0.0;
     for (int i = 0; i < nprev; ++i) s2 += partial_prev[i];
@@ -58,23 +59,20 @@ __global__ __launch_bounds__(256) void square_kernel(const double* __restrict__ 
     const double sc = 1.0 / (nrm * nrm);
     double ss = 0.0;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int r = row0 + 2 * ty + i, c = col0 + 2 * tx + j;
-            if (r < n && c < n) {
-                const double v = acc[i][j] * sc;
-                out[(size_t)r * n + c] = v;
-                ss += v * v;
-            }
+    for (int v = 0; v < 4; ++v) {
+        const int rr = row0 + 4 * q + v, cc = col0 + r;
+        if (rr < n && cc < n) {
+            const double val = acc[v] * sc;
+            out[(size_t)rr * n + cc] = val;
+            ss += val * val;
         }
-    red[tid] = ss;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) red[tid] += red[tid + s];
-        __syncthreads();
     }
-    if (tid == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = red[0];
+    // fixed-order sums: lanes of a wave by halving distances, then the four waves in index order
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) ss += __shfl_down(ss, d, 64);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    if (tid == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
 }
 
 __global__ void norm_kernel(const double* __restrict__ partial, int nblocks, double* __restrict__ norm_out) {
@@ -109,7 +107,7 @@ struct DeviceBuffers {
 
 hipError_t spectral_radius_device(const double* A, int n, double* rho_out) {
     constexpr int kMaxSquarings = 48;    // 2^-48 |log ||B^2||| is below double rounding of log rho
-    constexpr int kBatch = 8;            // squarings enqueued between two looks at the norms
+    constexpr int kBatch = 16;           // squarings enqueued between two looks at the norms
     double nf2 = 0.0;
     for (size_t i = 0; i < (size_t)n * n; ++i) nf2 += A[i] * A[i];
     const double nf = std::sqrt(nf2);
