@@ -22,8 +22,8 @@ typedef double doublex4 __attribute__((ext_vector_type(4)));
 // every work-group, so all of them scale by the same value); partial[block] = sum of squares of the
 // block's entries of out; work-group (0, 0) also stores ||M||_F in norm_slot[0].
 // The product runs on the float64 matrix instruction (16 x 16 x 4): lane (r = lane % 16, q = lane / 16)
-// supplies M[row0 + r][4s + q] and M[4s + q][col0 + r] for k-step s and holds rows 4q .. 4q+3, column r of
-// the 16 x 16 result.  Operands come straight from L2 (a 100 x 100 matrix is 80 KB), eight k-steps of
+// supplies M[row0 + r][4s + q] and M[4s + q][col0 + r] for k-step s; its result register v is row 4v + q,
+// column r of the 16 x 16 tile (the float64 form interleaves the rows, unlike the float32 one).  Operands come straight from L2 (a 100 x 100 matrix is 80 KB), eight k-steps of
 // loads in flight: a squaring of the chain of 48 is then little more than a launch and one round of loads.
 __global__ __launch_bounds__(256) void square_kernel(const double* __restrict__ M, double* __restrict__ out,
                                                      int n, const double* __restrict__ partial_prev, int nprev,
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void square_kernel(const double* __restrict__ 
     double ss = 0.0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int rr = row0 + 4 * q + v, cc = col0 + r;
+        const int rr = row0 + 4 * v + q, cc = col0 + r;
         if (rr < n && cc < n) {
             const double val = acc[v] * sc;
             out[(size_t)rr * n + cc] = val;

@@ -245,7 +245,7 @@ def test_split_mode_argument_errors_and_awkward_weight_ranges(elm):
         model.close()
 
 
-@pytest.mark.parametrize("L", [63, 64, 100, 257, 512])
+@pytest.mark.parametrize("L", [63, 64, 65, 100, 130, 257, 512])
 def test_spectral_radius_scaling_matches_the_oracle(elm, L):
     # below 64 columns the radius is computed on the host, from 64 on by the device kernels; the
     # oracle uses numpy's eigenvalues
