@@ -17,6 +17,14 @@ constexpr int kTileRows = 32;
 
 // ---- triangular solves on one work-group: blocks of 32, diagonal block by one wave in registers
 // y (LDS, doubles, length >= 32*ceil(L/32)) is overwritten by the solution of R11 x = y.
+// lane k's value in every lane (k is a constant after unrolling: two scalar broadcasts instead of a trip
+// through the LDS crossbar, on the critical path of every elimination step)
+__device__ __forceinline__ double lane_value(double v, int k) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), k);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), k);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ void solve_upper(const float* __restrict__ R, int np, int L, double* y) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int nb = (L + 31) / 32;
@@ -33,9 +41,14 @@ __device__ void solve_upper(const float* __restrict__ R, int np, int L, double* 
                 drow[l] = v;
             }
             double yi = (row < L) ? y[row] : 0.0;
+            double diag = 1.0;                 // this lane's diagonal entry; its reciprocal is taken off the chain
+#pragma unroll
+            for (int l = 0; l < 32; ++l)
+                if (l == i) diag = drow[l];
+            const double dinv = 1.0 / diag;
 #pragma unroll
             for (int k = 31; k >= 0; --k) {
-                const double xk = __shfl(yi, k) / __shfl(drow[k], k);
+                const double xk = lane_value(yi, k) * lane_value(dinv, k);
                 if (i == k) yi = xk;
                 else if (i < k) yi -= drow[k] * xk;
             }
@@ -70,9 +83,14 @@ __device__ void solve_upper_transposed(const float* __restrict__ R, int np, int 
                 dcol[l] = v;
             }
             double yi = (col < L) ? y[col] : 0.0;
+            double diag = 1.0;
+#pragma unroll
+            for (int l = 0; l < 32; ++l)
+                if (l == i) diag = dcol[l];
+            const double dinv = 1.0 / diag;
 #pragma unroll
             for (int k = 0; k < 32; ++k) {
-                const double xk = __shfl(yi, k) / __shfl(dcol[k], k);
+                const double xk = lane_value(yi, k) * lane_value(dinv, k);
                 if (i == k) yi = xk;
                 else if (i > k) yi -= dcol[k] * xk;
             }
