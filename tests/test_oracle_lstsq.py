@@ -127,3 +127,61 @@ def test_rmse_definition_multi_output():
     H, T = problem(80, 5, 3, seed=14)
     beta, rss, _ = lstsq.solve(H, T)
     assert abs(lstsq.rmse_from_rss(rss, 80, 3) - np.sqrt(np.mean((H @ beta - T) ** 2))) < 1e-13
+
+
+def test_normal_equation_residual_on_non_solutions_with_loops():
+    """The measure itself, away from zero: ||H^T r||_F / (||H||_F ||r||_F) with r = H beta - T written out
+    entry by entry.  A version that dropped a factor, a norm or the transpose would pass where the
+    residual vanishes and fail here."""
+    rng = np.random.default_rng(21)
+    N, L, m = 7, 3, 2
+    H = rng.standard_normal((N, L))
+    T = rng.standard_normal((N, m))
+    for beta in (np.zeros((L, m)), rng.standard_normal((L, m)), 10.0 * np.ones((L, m))):
+        r = [[sum(H[i, j] * beta[j, c] for j in range(L)) - T[i, c] for c in range(m)] for i in range(N)]
+        g2 = sum(sum(H[i, j] * r[i][c] for i in range(N)) ** 2 for j in range(L) for c in range(m))
+        h2 = sum(H[i, j] ** 2 for i in range(N) for j in range(L))
+        r2 = sum(r[i][c] ** 2 for i in range(N) for c in range(m))
+        want = (g2 ** 0.5) / ((h2 ** 0.5) * (r2 ** 0.5))
+        got = lstsq.normal_equation_residual(H, T, beta)
+        assert want > 1e-2                                  # far from a solution
+        assert abs(got - want) <= 1e-14 * want
+    # a hand case: H = e_1 (one column), T = (1, 1), beta = 0  ->  r = -T, H^T r = -1, ||H|| = 1, ||r|| = sqrt 2
+    assert abs(lstsq.normal_equation_residual(np.array([[1.0], [0.0]]), np.array([1.0, 1.0]), np.zeros((1, 1)))
+               - 1.0 / np.sqrt(2.0)) < 1e-15
+    # scale invariance in H and in (beta, T) jointly
+    beta = rng.standard_normal((L, m))
+    base = lstsq.normal_equation_residual(H, T, beta)
+    assert abs(lstsq.normal_equation_residual(3.0 * H, 3.0 * T, beta) - base) < 1e-14
+    # a 1-d target is a single column
+    assert abs(lstsq.normal_equation_residual(H, T[:, 0], beta[:, :1])
+               - lstsq.normal_equation_residual(H, T[:, :1], beta[:, :1])) == 0.0
+
+
+def test_rank_check_threshold_is_float32_epsilon_times_the_largest_diagonal():
+    """min|R_jj| <= 2^-23 max|R_jj| is rank deficient, anything above is not; signs do not matter and the
+    off-diagonal part is not looked at."""
+    eps32 = 2.0 ** -23
+    for dmax in (1.0, 37.5, 1e-6):
+        for sign in (1.0, -1.0):
+            R = np.triu(np.full((4, 4), 9.0))
+            np.fill_diagonal(R, [dmax, -0.5 * dmax, sign * eps32 * dmax * (1.0 + 1e-9), 0.25 * dmax])
+            lstsq.rank_check(R)                                         # just above: accepted
+            R[2, 2] = sign * eps32 * dmax                               # at the threshold: rejected
+            with pytest.raises(lstsq.RankDeficient):
+                lstsq.rank_check(R)
+            R[2, 2] = sign * eps32 * dmax * (1.0 - 1e-9)                # just below
+            with pytest.raises(lstsq.RankDeficient):
+                lstsq.rank_check(R)
+    # through solve(): two columns that differ by a relative 2^-20 pass, by 2^-26 of the scale fail
+    rng = np.random.default_rng(22)
+    H = rng.standard_normal((40, 3))
+    T = rng.standard_normal((40, 1))
+    e = rng.standard_normal(40)
+    e -= H[:, 0] * (H[:, 0] @ e) / (H[:, 0] @ H[:, 0])                  # orthogonal to column 0
+    e *= np.linalg.norm(H[:, 0]) / np.linalg.norm(e)
+    H[:, 2] = H[:, 0] + 2.0 ** -14 * e
+    lstsq.solve(H, T)
+    H[:, 2] = H[:, 0] + 2.0 ** -26 * e
+    with pytest.raises(lstsq.RankDeficient):
+        lstsq.solve(H, T)

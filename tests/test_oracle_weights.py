@@ -79,3 +79,51 @@ def test_forget_bias_and_zero_bias():
     assert np.all(bz == 0.0)
     np.testing.assert_array_equal(Wz, Wn)
     np.testing.assert_array_equal(Uz, Un)
+
+
+def _scalar_stream(seed, a):
+    """The generator written out with Python integers, one value per call."""
+    mask = (1 << 64) - 1
+    state = seed & mask
+    while True:
+        state = (state + 0x9E3779B97F4A7C15) & mask
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        z ^= z >> 31
+        yield (2.0 * ((z >> 11) / 2.0 ** 53) - 1.0) * a
+
+
+@pytest.mark.parametrize("cell", ["elman_diag", "fc_multilag"])
+def test_multilag_cells_shape_and_stream_order_against_a_scalar_stream(cell):
+    """alpha [L, Q] (lag k in column k-1) and A [Q, L, L] (lag k in block k-1, A[k-1][m][j]) take U's place
+    in the stream: W row-major first, then the recurrent array row-major, then b; a wrong axis order or a
+    swapped draw order moves values and fails the element-wise comparison."""
+    d, L, Q, a, seed = 2, 3, 4, 0.25, 99
+    W, U, b = weights.draw(cell, d, L, seed=seed, w_scale=a, Q=Q)
+    g = _scalar_stream(seed, a)
+    Wr = np.empty((d, L)); br = np.empty(L)
+    for s in range(d):
+        for j in range(L):
+            Wr[s, j] = next(g)
+    if cell == "elman_diag":
+        Ur = np.empty((L, Q))
+        for j in range(L):
+            for k in range(Q):
+                Ur[j, k] = next(g)
+    else:
+        Ur = np.empty((Q, L, L))
+        for k in range(Q):
+            for mm in range(L):
+                for j in range(L):
+                    Ur[k, mm, j] = next(g)
+    for j in range(L):
+        br[j] = next(g)
+    assert W.shape == Wr.shape and U.shape == Ur.shape and b.shape == br.shape
+    np.testing.assert_array_equal(W, Wr.astype(np.float32))
+    np.testing.assert_array_equal(U, Ur.astype(np.float32))
+    np.testing.assert_array_equal(b, br.astype(np.float32))
+    # the non-square shapes make a transposed draw visible
+    assert not np.array_equal(U.reshape(-1), np.swapaxes(U, -1, -2).reshape(-1))
+    with pytest.raises(ValueError):
+        weights.draw(cell, d, L, seed=seed, w_scale=a)          # the multi-lag cells need Q
