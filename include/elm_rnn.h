@@ -12,14 +12,23 @@
  * General conventions
  *   - Every function returns 0 (ELM_OK) or a negative error code; nothing
  *     throws across this boundary.  elm_rnn_strerror() names a code and
- *     elm_rnn_last_hip_error() returns the text of the last HIP failure.
+ *     elm_rnn_last_hip_error() returns the text of the calling thread's last
+ *     HIP failure (or the reason of its last ELM_EUNSUPPORTED, where one is given).
  *   - "device" pointers are HIP device memory on the current device, owned by
  *     the caller; the library never frees them and allocates no O(N) memory.
- *     "host" pointers are ordinary memory.  A model owns only its small weight
- *     and beta buffers on the device.
- *   - All work is enqueued on the caller's stream (hip_stream: a hipStream_t
- *     cast to void*, NULL = the default stream).  Functions that return values
- *     to the host (stats) synchronise that stream before returning.
+ *     "host" pointers are ordinary memory.  A model owns only its weight
+ *     and beta buffers on the device (the packed lag matrices of the multi-lag
+ *     cell are its largest: Q L^2 floats); every scratch buffer whose size
+ *     grows with N comes from the caller's workspace, so calls on one model
+ *     with different workspaces may overlap in time.
+ *   - All device work of the functions that take hip_stream (a hipStream_t
+ *     cast to void*, NULL = the default stream) is enqueued on that stream,
+ *     the weight generation inside the two fit functions included.  Functions
+ *     that return values to the host (stats) synchronise it before returning.
+ *     The functions without a stream argument (model creation, weight and
+ *     beta copies) use synchronous copies and, for Elman layers of 64 units
+ *     or more with a spectral-radius target, kernels on the default stream,
+ *     and return when their work is done.
  *   - Matrices are row-major float32 unless stated.  X[i, t, :] (sample i, step
  *     t, d contiguous channels) lives at X + i*ldx_n + t*ldx_q (strides in
  *     elements): materialised windows use ldx_n = Q*d, ldx_q = d; zero-copy
@@ -61,10 +70,9 @@ extern "C" {
                                 ago, into neuron j; the last block is never used); no initial state,
                                 Q_run <= Q.  While the history of a window is short (max(Q-1,1)*L + d + 1
                                 <= 1272, and <= 640 for L <= 64) it stays on chip for all steps; beyond
-                                that every step is a launch of its own over a device buffer of past
-                                states that the model owns (allocated at creation, below 2 GiB: room for
-                                up to 65,536 rows, more rows are taken in passes).  Calls that build H
-                                from one such model must not overlap in time (they share that buffer).
+                                that every step is a launch of its own over a buffer of past states in
+                                the caller's workspace (elm_rnn_hidden_workspace_bytes: below 2 GiB, room
+                                for up to 65,536 rows, more rows are taken in passes).
                                 ELM_EUNSUPPORTED if a window's history reaches 8 MiB or the packed lag
                                 matrices 4 GiB                                                       */
 
@@ -90,8 +98,8 @@ extern "C" {
 
 typedef struct elm_rnn_model elm_rnn_model;   /* opaque; from *_create or fit, released by elm_rnn_free */
 
-/* How step (1) of Algorithm "S-R-ELM" draws the weights ("Randomly assign W, alpha, b").
- * A SplitMix64 stream seeded with `seed` yields u in [0,1) with 53 bits; each value is
+/* How step (1) of Algorithm "S-R-ELM" (the random assignment of the input, recurrent and bias
+ * weights) draws its values.  A SplitMix64 stream seeded with `seed` yields u in [0,1) with 53 bits; each value is
  * (2u-1)*w_scale in double; draw order W (row-major), U (row-major), b; then
  *   spectral_radius > 0 (Elman only): U *= spectral_radius / max|eig(U)|
  *   zero_bias != 0: b = 0 (the draws are still consumed), else
@@ -147,14 +155,24 @@ void elm_rnn_free(elm_rnn_model* model);
 
 /* ---- step (2): H(Q) ------------------------------------------------------------------------ */
 
+/* Device scratch elm_rnn_hidden needs for N rows of a (cell, Q, d, L) model: 0 for every cell whose
+ * per-step states stay on chip, i.e. all but ELM_CELL_FC_MULTILAG beyond its on-chip limit, where it is
+ * the history of a pass of rows (min(N rounded up to 256, 65,536) x (Q-1) x L rounded up to 8 floats)
+ * plus carried sums.  It never decreases when N grows.  0 also for unsupported sizes. */
+size_t elm_rnn_hidden_workspace_bytes(int cell, int64_t N, int Q, int d, int L);
+
 /* Unroll N windows through the model's cell for Q_run steps (1 <= Q_run; X must hold that many
  * steps) and write the final hidden state of sample i to H_out[i*L .. i*L+L) (device).  h0 / c0
  * (device, N x L, nullable = zero) give the state before the first step; c0 and c_out (nullable)
- * are used by the LSTM only.  Only H(Q) is produced: the per-step states never leave the chip
- * (step 3 of Algorithm "S-R-ELM" uses H(Q) alone). */
+ * are used by the LSTM only.  Only H(Q) is produced: for the lag-1 cells the per-step states never
+ * leave the chip (step 3 of Algorithm "S-R-ELM" uses H(Q) alone).  workspace (device, contents
+ * destroyed) must hold elm_rnn_hidden_workspace_bytes() for the model's sizes and N, else
+ * ELM_EWORKSPACE; it may be NULL where that is 0.  The model is only read: calls with different
+ * workspaces and outputs may run concurrently on different streams. */
 int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
                    int64_t N, int Q_run, const float* h0, const float* c0,
-                   float* H_out, float* c_out, void* hip_stream);
+                   float* H_out, float* c_out, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
 
 /* ---- step (3): beta = H^+ T ---------------------------------------------------------------- */
 
@@ -163,8 +181,11 @@ size_t elm_rnn_solve_workspace_bytes(int64_t N, int L, int m);
 
 /* Least squares min ||H beta - T||_F for device H (N x L) and T (N x m), N >= L.
  * Blocked Householder TSQR of [H | T] in float32 (the paper's H = QR, z = Q^T Y), back
- * substitution R beta = z, then `refine` (0..4; the library default is 2) steps of iterative
- * refinement whose residual T - H beta and gradient H^T r are accumulated in float64.
+ * substitution R beta = z, then `refine` steps of iterative refinement whose residual T - H beta
+ * and gradient H^T r are accumulated in float64: refine = 0..4 steps, or -1 = two steps if
+ * max|R_jj| > 30 min|R_jj| (the normal-equation residual of the unrefined solution is about
+ * 1e-8 .. 6e-8 times that ratio) and none otherwise.  One more pass over H gives the statistics
+ * of the returned beta.
  * beta_out (device, L x m float32) and beta64_out (device, L x m float64, nullable) receive
  * the result; stats (host, nullable) is filled after a stream synchronisation.
  * Returns ELM_ERANK (after writing outputs) if H is numerically rank deficient. */
@@ -174,16 +195,17 @@ int elm_rnn_solve(const float* H, const float* T, int64_t N, int L, int m, int r
 
 /* ---- the whole fit -------------------------------------------------------------------------- */
 
-/* Workspace for elm_rnn_fit: the solve workspace, plus N*L floats when H_out is NULL. */
-size_t elm_rnn_fit_workspace_bytes(int64_t N, int L, int m, int h_in_workspace);
+/* Workspace for elm_rnn_fit: the solve workspace, plus N*L floats when H_out is NULL, plus
+ * elm_rnn_hidden_workspace_bytes(cell, N, Q, d, L).  0 for unsupported sizes. */
+size_t elm_rnn_fit_workspace_bytes(int cell, int64_t N, int Q, int d, int L, int m, int h_in_workspace);
 
 /* Algorithm "S-R-ELM" end to end: create the model from `seed`, build H(Q) from the device
  * windows X, solve for beta against the device targets T (N x m), keep beta in the model.
- * H_out (device, N x L) is nullable (then H lives in the workspace).  beta_out / beta64_out /
- * stats as in elm_rnn_solve.  *model_out receives the model (also on ELM_ERANK). */
+ * H_out (device, N x L) is nullable (then H lives in the workspace).  refine / beta_out /
+ * beta64_out / stats as in elm_rnn_solve.  *model_out receives the model (also on ELM_ERANK). */
 int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T,
                 int64_t N, int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
-                void* workspace, size_t workspace_bytes, void* hip_stream,
+                int refine, void* workspace, size_t workspace_bytes, void* hip_stream,
                 float* H_out, float* beta_out, double* beta64_out,
                 elm_rnn_stats* stats, elm_rnn_model** model_out);
 
@@ -191,8 +213,9 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
 
 /* Workspace for elm_rnn_fit_streamed: the solve workspace plus one chunk of H (chunk_rows x L floats;
  * chunk_rows <= 0 selects the default, about 128 MiB of H; other values are rounded up to a multiple of
- * 128 rows and capped at N). */
-size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows);
+ * 128 rows and capped at N) plus elm_rnn_hidden_workspace_bytes() for a chunk of rows. */
+size_t elm_rnn_fit_streamed_workspace_bytes(int cell, int64_t N, int Q, int d, int L, int m,
+                                            int64_t chunk_rows);
 
 /* Algorithm "S-R-ELM" with steps (2) and (3) fused: only H(Q) enters step (3), and the R factor of
  * [H | T] can absorb H a block of rows at a time, so the N x L matrix never exists.  Two forms:
@@ -226,13 +249,14 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
                          void* hip_stream, float* beta_out, double* beta64_out,
                          elm_rnn_stats* stats, elm_rnn_model** model_out);
 
-/* Workspace with which elm_rnn_predict runs in one pass: N*L floats for H. */
-size_t elm_rnn_predict_workspace_bytes(int64_t N, int L);
+/* Workspace with which elm_rnn_predict runs in one pass: N*L floats for H plus the model's
+ * elm_rnn_hidden_workspace_bytes() for N rows. */
+size_t elm_rnn_predict_workspace_bytes(const elm_rnn_model* model, int64_t N);
 
 /* The paper's output equation y_hat = sum_i beta_i f_i(Q): build H(Q) for N new windows with
  * the model's weights and write Y_out = H beta (device, N x m float32).  A smaller workspace is
- * accepted as long as it holds 256 rows of H (or all N): H is then produced and consumed in chunks of as
- * many rows as fit, with the same result. */
+ * accepted as long as it holds elm_rnn_predict_workspace_bytes() for 256 rows (or for all N): H is then
+ * produced and consumed in chunks of as many rows as fit, with the same result. */
 int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
                     int64_t N, float* Y_out, void* workspace, size_t workspace_bytes,
                     void* hip_stream);

@@ -15,7 +15,8 @@ ELM_OK, ELM_EINVAL, ELM_EWORKSPACE, ELM_ERANK, ELM_EHIP, ELM_EUNSUPPORTED = 0, -
 
 DECLARED_SYMBOLS = (
     "elm_rnn_model_create", "elm_rnn_model_create_from_weights", "elm_rnn_get_weights",
-    "elm_rnn_model_set_contraction", "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
+    "elm_rnn_model_set_contraction", "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden_workspace_bytes",
+    "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
     "elm_rnn_solve", "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
     "elm_rnn_fit_streamed_workspace_bytes", "elm_rnn_fit_streamed",
     "elm_rnn_predict_workspace_bytes", "elm_rnn_predict", "elm_rnn_strerror",
@@ -85,20 +86,22 @@ def load_library():
     lib.elm_rnn_model_set_contraction.argtypes = [vp, C.c_int]
     lib.elm_rnn_free.argtypes = [vp]
     lib.elm_rnn_free.restype = None
-    lib.elm_rnn_hidden.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp]
+    lib.elm_rnn_hidden_workspace_bytes.argtypes = [C.c_int, i64, C.c_int, C.c_int, C.c_int]
+    lib.elm_rnn_hidden_workspace_bytes.restype = sz
+    lib.elm_rnn_hidden.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.elm_rnn_solve_workspace_bytes.argtypes = [i64, C.c_int, C.c_int]
     lib.elm_rnn_solve_workspace_bytes.restype = sz
     lib.elm_rnn_solve.argtypes = [vp, vp, i64, C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(_Stats), vp, sz, vp]
-    lib.elm_rnn_fit_workspace_bytes.argtypes = [i64, C.c_int, C.c_int, C.c_int]
+    lib.elm_rnn_fit_workspace_bytes.argtypes = [C.c_int, i64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     lib.elm_rnn_fit_workspace_bytes.restype = sz
     lib.elm_rnn_fit.argtypes = [C.c_int, vp, i64, i64, vp, i64, C.c_int, C.c_int, C.c_int, C.c_int, u64,
-                                C.POINTER(_Init), vp, sz, vp, vp, vp, vp, C.POINTER(_Stats), C.POINTER(vp)]
-    lib.elm_rnn_fit_streamed_workspace_bytes.argtypes = [i64, C.c_int, C.c_int, i64]
+                                C.POINTER(_Init), C.c_int, vp, sz, vp, vp, vp, vp, C.POINTER(_Stats), C.POINTER(vp)]
+    lib.elm_rnn_fit_streamed_workspace_bytes.argtypes = [C.c_int, i64, C.c_int, C.c_int, C.c_int, C.c_int, i64]
     lib.elm_rnn_fit_streamed_workspace_bytes.restype = sz
     lib.elm_rnn_fit_streamed.argtypes = [C.c_int, vp, i64, i64, vp, i64, C.c_int, C.c_int, C.c_int, C.c_int, u64,
                                          C.POINTER(_Init), i64, C.c_int, vp, sz, vp, vp, vp, C.POINTER(_Stats),
                                          C.POINTER(vp)]
-    lib.elm_rnn_predict_workspace_bytes.argtypes = [i64, C.c_int]
+    lib.elm_rnn_predict_workspace_bytes.argtypes = [vp, i64]
     lib.elm_rnn_predict_workspace_bytes.restype = sz
     lib.elm_rnn_predict.argtypes = [vp, vp, i64, i64, i64, vp, vp, sz, vp]
     lib.elm_rnn_probe_workspace_bytes.argtypes = []
@@ -224,8 +227,12 @@ class Model:
             pass
 
 
+def hidden_workspace_bytes(cell: str, N: int, Q: int, d: int, L: int) -> int:
+    return int(load_library().elm_rnn_hidden_workspace_bytes(CELLS[cell], N, Q, d, L))
+
+
 def hidden(model: Model, X, Q_run: Optional[int] = None, h0=None, c0=None, out=None, c_out=None,
-           stream=None):
+           workspace=None, stream=None):
     """elm_rnn_hidden: H(Q_run) [N, L] for device windows X [N, Q, d]."""
     import torch
     lib = load_library()
@@ -245,10 +252,15 @@ def hidden(model: Model, X, Q_run: Optional[int] = None, h0=None, c0=None, out=N
                 raise ValueError(f"{name} must be a contiguous [N, L] tensor")
     if tuple(H.shape) != (N, model.L) or not H.is_contiguous():
         raise ValueError("out must be a contiguous [N, L] tensor")
+    if workspace is None:
+        need = hidden_workspace_bytes(model.cell, N, model.Q, model.d, model.L)
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device) if need else None
     _check(lib.elm_rnn_hidden(model._h, X.data_ptr(), ldn, ldq, N, q,
                               None if h0 is None else h0.data_ptr(),
                               None if c0 is None else c0.data_ptr(), H.data_ptr(),
-                              None if c_out is None else c_out.data_ptr(), _stream_ptr(stream)))
+                              None if c_out is None else c_out.data_ptr(),
+                              None if workspace is None else workspace.data_ptr(),
+                              0 if workspace is None else workspace.numel(), _stream_ptr(stream)))
     return H
 
 
@@ -256,8 +268,17 @@ def solve_workspace_bytes(N: int, L: int, m: int) -> int:
     return int(load_library().elm_rnn_solve_workspace_bytes(N, L, m))
 
 
-def fit_workspace_bytes(N: int, L: int, m: int, h_in_workspace: bool) -> int:
-    return int(load_library().elm_rnn_fit_workspace_bytes(N, L, m, int(h_in_workspace)))
+def fit_workspace_bytes(N: int, L: int, m: int, h_in_workspace: bool, cell: str = "elman", Q: int = 1,
+                        d: int = 1) -> int:
+    """elm_rnn_fit_workspace_bytes; only the launch-per-step multi-lag cell depends on (cell, Q, d)."""
+    return int(load_library().elm_rnn_fit_workspace_bytes(CELLS[cell], N, Q, d, L, m, int(h_in_workspace)))
+
+
+def _release_on_error(rc: int, handle, allow_rank: bool) -> None:
+    """A fit hands back a live model on ELM_ERANK too: free it when that code is about to be raised."""
+    if rc != ELM_OK and not (allow_rank and rc == ELM_ERANK) and handle.value:
+        load_library().elm_rnn_free(handle)
+        handle.value = None
 
 
 def solve(H, T, refine: int = 2, workspace=None, stream=None, allow_rank_deficient: bool = False):
@@ -294,8 +315,8 @@ class FitResult:
 
 
 def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0, forget_bias=0.0,
-        zero_bias=False, contraction="fp32", keep_H: bool = True, workspace=None, H_out=None, stream=None,
-        allow_rank_deficient: bool = False) -> FitResult:
+        zero_bias=False, contraction="fp32", refine: int = -1, keep_H: bool = True, workspace=None, H_out=None,
+        stream=None, allow_rank_deficient: bool = False) -> FitResult:
     """elm_rnn_fit: Algorithm "S-R-ELM" end to end on device tensors X [N,Q,d], T [N,m]."""
     import torch
     lib = load_library()
@@ -309,9 +330,13 @@ def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0,
     m = T.shape[1]
     ldn, ldq = _x_strides(X)
     H = H_out
+    if H is not None:
+        _dev_f32(H, "H_out")
+        if tuple(H.shape) != (N, L) or not H.is_contiguous():
+            raise ValueError("H_out must be a contiguous [N, L] tensor")
     if H is None and keep_H:
         H = torch.empty((N, L), dtype=torch.float32, device=X.device)
-    need = fit_workspace_bytes(N, L, m, H is None)
+    need = fit_workspace_bytes(N, L, m, H is None, cell, Q, d)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     beta32 = torch.empty((L, m), dtype=torch.float32, device=X.device)
@@ -320,15 +345,18 @@ def fit(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0,
     out = C.c_void_p()
     init = _init_struct(w_scale, spectral_radius, forget_bias, zero_bias, contraction)
     rc = lib.elm_rnn_fit(CELLS[cell], X.data_ptr(), ldn, ldq, T.data_ptr(), N, Q, d, L, m, C.c_uint64(seed),
-                         C.byref(init), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream),
+                         C.byref(init), refine, workspace.data_ptr(), workspace.numel(), _stream_ptr(stream),
                          None if H is None else H.data_ptr(), beta32.data_ptr(), beta64.data_ptr(),
                          C.byref(st), C.byref(out))
+    _release_on_error(rc, out, allow_rank_deficient)
     _check(rc, allow_rank=allow_rank_deficient)
     return FitResult(Model(out.value, cell, Q, d, L, m), beta32, beta64, H, _stats(st, rc == ELM_ERANK))
 
 
-def fit_streamed_workspace_bytes(N: int, L: int, m: int, chunk_rows: int = 0) -> int:
-    return int(load_library().elm_rnn_fit_streamed_workspace_bytes(N, L, m, chunk_rows))
+def fit_streamed_workspace_bytes(N: int, L: int, m: int, chunk_rows: int = 0, cell: str = "elman", Q: int = 1,
+                                 d: int = 1) -> int:
+    """elm_rnn_fit_streamed_workspace_bytes; only the launch-per-step multi-lag cell depends on (cell, Q, d)."""
+    return int(load_library().elm_rnn_fit_streamed_workspace_bytes(CELLS[cell], N, Q, d, L, m, chunk_rows))
 
 
 def fit_streamed(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_radius=0.0, forget_bias=0.0,
@@ -346,7 +374,7 @@ def fit_streamed(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_ra
     N, Q, d = X.shape
     m = T.shape[1]
     ldn, ldq = _x_strides(X)
-    need = fit_streamed_workspace_bytes(N, L, m, chunk_rows)
+    need = fit_streamed_workspace_bytes(N, L, m, chunk_rows, cell, Q, d)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     beta32 = torch.empty((L, m), dtype=torch.float32, device=X.device)
@@ -358,6 +386,7 @@ def fit_streamed(cell: str, X, T, L: int, seed: int, *, w_scale=1.0, spectral_ra
                                   C.c_uint64(seed), C.byref(init), chunk_rows, refine, workspace.data_ptr(),
                                   workspace.numel(), _stream_ptr(stream), beta32.data_ptr(), beta64.data_ptr(),
                                   C.byref(st), C.byref(out))
+    _release_on_error(rc, out, allow_rank_deficient)
     _check(rc, allow_rank=allow_rank_deficient)
     return FitResult(Model(out.value, cell, Q, d, L, m), beta32, beta64, None, _stats(st, rc == ELM_ERANK))
 
@@ -383,7 +412,12 @@ def predict(model: Model, X, workspace=None, stream=None):
         raise ValueError("X does not match the model")
     ldn, ldq = _x_strides(X)
     if workspace is None:      # one pass when H is small, else chunks of about 128 MiB of H
-        need = min(int(lib.elm_rnn_predict_workspace_bytes(N, model.L)), 128 << 20)
+        need = int(lib.elm_rnn_predict_workspace_bytes(model._h, N))
+        if need > (128 << 20):
+            rows = max(256, (128 << 20) // (4 * model.L) // 256 * 256)
+            if hidden_workspace_bytes(model.cell, N, model.Q, model.d, model.L) > 0:
+                rows = 65536                      # whole passes of the launch-per-step multi-lag cell
+            need = int(lib.elm_rnn_predict_workspace_bytes(model._h, min(N, rows)))
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     Y = torch.empty((N, model.m), dtype=torch.float32, device=X.device)
     _check(lib.elm_rnn_predict(model._h, X.data_ptr(), ldn, ldq, N, Y.data_ptr(), workspace.data_ptr(),

@@ -19,9 +19,8 @@ struct elm_rnn_model {
     float* dDiag = nullptr;       // ELM_CELL_ELMAN_DIAG: W^T [L][d], alpha [L][Q], b [L] back to back
     elm::FcStepLayout fcs{};      // ELM_CELL_FC_MULTILAG beyond what LDS holds: one launch per step with
     float* dFcW = nullptr;        //   the packed stack [A_{Q-1}; ...; A_1; W; b] and
-    float* dFcW16 = nullptr;      //   the same stack per 16-column unit (layers of 65 to 96 units)
-    float* dFcHist = nullptr;     //   the past states of a chunk of rows (scratch of every hidden-matrix call)
-    float* dFcSums = nullptr;     //   and sums carried over a block of steps or split over slices of a contraction
+    float* dFcW16 = nullptr;      //   the same stack per 16-column unit (layers of 65 to 96 units);
+                                  //   the past states of a pass of rows live in the caller's workspace
     int contraction = ELM_CONTRACT_FP32;
     elm::SplitLayout slay{};      // ELM_CONTRACT_SPLIT16: layout and packed split weights
     void* dWs = nullptr;
@@ -34,6 +33,16 @@ static thread_local char g_hip_error[512] = "";
 
 void set_hip_error(hipError_t e, const char* where) {
     std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", where, hipGetErrorString(e));
+}
+
+void set_error_text(const char* text) { std::snprintf(g_hip_error, sizeof g_hip_error, "%s", text); }
+
+int device_compute_units() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return 256;
+    return cus;
 }
 
 namespace {
@@ -173,8 +182,6 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
         e = hipMalloc(&mdl->dTiny, tiny.size() * sizeof(float));
         if (e == hipSuccess) e = hipMemcpy(mdl->dTiny, tiny.data(), tiny.size() * sizeof(float), hipMemcpyHostToDevice);
     }
-    if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcHist, mdl->fcs.hist_floats * sizeof(float));
-    if (e == hipSuccess && dst == &mdl->dFcW) e = hipMalloc(&mdl->dFcSums, mdl->fcs.sums_floats * sizeof(float));
     if (e == hipSuccess && dst == &mdl->dFcW && mdl->fcs.NU > 0) {
         std::vector<float> units(mdl->fcs.floats16);
         pack_weights_fc_rows(mdl->fcs, mdl->W.data(), mdl->U.data(), mdl->b.data(), units.data());
@@ -185,7 +192,10 @@ int build_model(int cell, int Q, int d, int L, int m, std::vector<float>&& W, st
     if (e == hipSuccess) e = hipMalloc(&mdl->dBeta, (size_t)L * m * sizeof(double));
     if (e == hipSuccess)
         e = hipMemcpy(*dst, packed.data(), packed.size() * sizeof(float), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemset(mdl->dBeta, 0, (size_t)L * m * sizeof(double));
+    if (e == hipSuccess) {        // beta = 0 until a fit stores it; a synchronous copy, so that it is ordered
+        const std::vector<double> zeros((size_t)L * m, 0.0);       // before work on any stream of the caller
+        e = hipMemcpy(mdl->dBeta, zeros.data(), zeros.size() * sizeof(double), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         set_hip_error(e, "model upload");
         elm_rnn_free(mdl);
@@ -209,9 +219,22 @@ int enable_split(elm_rnn_model* mdl) {
     return ELM_OK;
 }
 
-// stage 1 for any cell
+// device scratch stage 1 needs for N rows of this model (only the launch-per-step multi-lag cell has any)
+size_t hidden_scratch_bytes(const elm_rnn_model* mdl, int64_t N) {
+    return mdl->dFcW != nullptr ? fc_scratch(mdl->fcs, N).bytes : 0;
+}
+
+// the same before a model exists
+size_t hidden_scratch_bytes(int cell, int64_t N, int Q, int d, int L) {
+    FcStepLayout lay{};
+    if (cell != ELM_CELL_FC_MULTILAG || N < 1 || fc_in_lds(Q, d, L) || !fc_step_layout(Q, d, L, &lay)) return 0;
+    return fc_scratch(lay, N).bytes;
+}
+
+// stage 1 for any cell; scratch: hidden_scratch_bytes(mdl, N) of device memory (may be null when that is 0)
 hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N,
-                      int Q_run, const float* h0, const float* c0, float* H, float* C, hipStream_t stream) {
+                      int Q_run, const float* h0, const float* c0, float* H, float* C, void* scratch,
+                      hipStream_t stream) {
     if (mdl->cell == ELM_CELL_ELMAN_DIAG) {
         const float* Wt = mdl->dDiag;
         const float* alpha = Wt + (size_t)mdl->L * mdl->d;
@@ -220,8 +243,7 @@ hipError_t run_hidden(const elm_rnn_model* mdl, const float* X, int64_t ldx_n, i
                                   stream);
     }
     if (mdl->dFcW != nullptr)
-        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcW16, mdl->dFcHist, mdl->dFcSums, X, ldx_n, ldx_q, N, Q_run, H,
-                                      stream);
+        return launch_hidden_fc_steps(mdl->fcs, mdl->dFcW, mdl->dFcW16, scratch, X, ldx_n, ldx_q, N, Q_run, H, stream);
     if (mdl->contraction == ELM_CONTRACT_FP32 && mdl->dTiny != nullptr)
         return launch_hidden_tiny(mdl->cell, mdl->d, mdl->L, mdl->dTiny, X, ldx_n, ldx_q, N, Q_run, h0, c0, H, C, stream);
     if (mdl->contraction == ELM_CONTRACT_SPLIT16 && mdl->dWs != nullptr)
@@ -242,16 +264,30 @@ struct EventPair {
     }
 };
 
+// max|R_jj| / min|R_jj| above which refine = -1 refines beta: the normal-equation residual of the unrefined
+// float32 solution grows like 1e-8 .. 6e-8 times this ratio
+constexpr double kAutoRefineRatio = 30.0;
+
 // stage 2 on the stream; fills stats (after a sync) when asked.  hidden_ms is copied through.
 int run_solve(const float* H, const float* T, int64_t N, int L, int m, int refine, float* beta_out,
               double* beta64_out, elm_rnn_stats* stats, void* ws, size_t ws_bytes,
               hipStream_t stream, double hidden_ms, hipEvent_t hidden_done) {
     if (H == nullptr || T == nullptr || beta_out == nullptr) return ELM_EINVAL;
-    if (N < 1 || L < 1 || m < 1 || N < L || refine < 0 || refine > 4) return ELM_EINVAL;
+    if (N < 1 || L < 1 || m < 1 || N < L || refine < -1 || refine > 4) return ELM_EINVAL;
     if (L > 512 || m > 16) return ELM_EUNSUPPORTED;
     const SolvePlan plan = make_solve_plan(N, L, m);
     if (ws == nullptr || ws_bytes < plan.bytes) return ELM_EWORKSPACE;
+    return run_solve_with_plan(plan, H, T, refine, beta_out, beta64_out, stats, ws, stream, hidden_ms, hidden_done);
+}
 
+}  // namespace
+
+// Stage 2 with a plan the caller made (ws holds plan.bytes): TSQR, back-solve, refinement, statistics.
+int run_solve_with_plan(const SolvePlan& plan, const float* H, const float* T, int refine, float* beta_out,
+                        double* beta64_out, elm_rnn_stats* stats, void* ws, hipStream_t stream,
+                        double hidden_ms, hipEvent_t hidden_done) {
+    const int64_t N = plan.N;
+    const int L = plan.L, m = plan.m;
     EventPair ev;
     ELM_HIP_TRY(ev.create());
     if (hidden_done == nullptr) ELM_HIP_TRY(hipEventRecord(ev.a, stream));
@@ -259,6 +295,13 @@ int run_solve(const float* H, const float* T, int64_t N, int L, int m, int refin
     float* R = nullptr;
     ELM_HIP_TRY(launch_tsqr(plan, H, T, ws, &R, stream));
     ELM_HIP_TRY(launch_backsolve(plan, R, ws, stream));
+    double sc[8];
+    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(ws) + plan.off_small);
+    if (refine < 0) {          // decide from the diagonal of R, which the back-solve has just recorded
+        ELM_HIP_TRY(hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream));
+        ELM_HIP_TRY(hipStreamSynchronize(stream));
+        refine = (sc[6] == 0.0 && sc[5] > kAutoRefineRatio * sc[4]) ? 2 : 0;
+    }
     for (int it = 0; it < refine; ++it) {
         ELM_HIP_TRY(launch_residual_pass(plan, H, T, ws, stream));
         ELM_HIP_TRY(launch_refine_update(plan, R, ws, stream));
@@ -268,8 +311,6 @@ int run_solve(const float* H, const float* T, int64_t N, int L, int m, int refin
     ELM_HIP_TRY(hipEventRecord(ev.b, stream));
 
     // the rank flag is always read back: the return code depends on it
-    double sc[8];
-    const double* small = reinterpret_cast<const double*>(static_cast<const char*>(ws) + plan.off_small);
     ELM_HIP_TRY(hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream));
     ELM_HIP_TRY(hipStreamSynchronize(stream));
     if (stats != nullptr) {
@@ -289,15 +330,15 @@ int run_solve(const float* H, const float* T, int64_t N, int L, int m, int refin
     return sc[6] != 0.0 ? ELM_ERANK : ELM_OK;
 }
 
-}  // namespace
 }  // namespace elm
 
 using namespace elm;
 
 extern "C" {
 
-int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
-                         const elm_rnn_init* init, elm_rnn_model** model_out) {
+// step 1 of Algorithm "S-R-ELM"; device work (the spectral radius of a wide Elman matrix) goes to `stream`
+static int create_model(int cell, int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
+                        hipStream_t stream, elm_rnn_model** model_out) {
     if (init == nullptr || model_out == nullptr) return ELM_EINVAL;
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
@@ -315,7 +356,7 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
         if (L < 64) {
             rho = spectral_radius(U, L);        // microseconds on the host
         } else {
-            ELM_HIP_TRY(spectral_radius_device(U.data(), L, &rho));
+            ELM_HIP_TRY(spectral_radius_device(U.data(), L, &rho, stream));
         }
         if (!(rho > 0.0)) return ELM_EINVAL;
         const double f = init->spectral_radius / rho;
@@ -336,6 +377,11 @@ int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
         }
     }
     return rc;
+}
+
+int elm_rnn_model_create(int cell, int Q, int d, int L, int m, uint64_t seed,
+                         const elm_rnn_init* init, elm_rnn_model** model_out) {
+    return create_model(cell, Q, d, L, m, seed, init, nullptr, model_out);
 }
 
 int elm_rnn_model_create_from_weights(int cell, int Q, int d, int L, int m, const float* W,
@@ -386,22 +432,27 @@ void elm_rnn_free(elm_rnn_model* model) {
     if (model->dDiag) (void)hipFree(model->dDiag);
     if (model->dFcW) (void)hipFree(model->dFcW);
     if (model->dFcW16) (void)hipFree(model->dFcW16);
-    if (model->dFcHist) (void)hipFree(model->dFcHist);
-    if (model->dFcSums) (void)hipFree(model->dFcSums);
     if (model->dWs) (void)hipFree(model->dWs);
     if (model->dBeta) (void)hipFree(model->dBeta);
     delete model;
 }
 
+size_t elm_rnn_hidden_workspace_bytes(int cell, int64_t N, int Q, int d, int L) {
+    if (check_dims(cell, Q, d, L, 1) != ELM_OK) return 0;
+    return hidden_scratch_bytes(cell, N, Q, d, L);
+}
+
 int elm_rnn_hidden(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
                    int64_t N, int Q_run, const float* h0, const float* c0, float* H_out,
-                   float* c_out, void* hip_stream) {
+                   float* c_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (model == nullptr || X == nullptr || H_out == nullptr) return ELM_EINVAL;
     if (N < 1 || Q_run < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    const size_t need = hidden_scratch_bytes(model, N);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return ELM_EWORKSPACE;
     if ((model->cell == ELM_CELL_ELMAN_DIAG || model->cell == ELM_CELL_FC_MULTILAG) &&
         (h0 != nullptr || c0 != nullptr || c_out != nullptr || Q_run > model->Q))
         return ELM_EINVAL;
-    ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out,
+    ELM_HIP_TRY(run_hidden(model, X, ldx_n, ldx_q, N, Q_run, h0, c0, H_out, c_out, workspace,
                            static_cast<hipStream_t>(hip_stream)));
     return ELM_OK;
 }
@@ -418,36 +469,41 @@ int elm_rnn_solve(const float* H, const float* T, int64_t N, int L, int m, int r
                      static_cast<hipStream_t>(hip_stream), 0.0, nullptr);
 }
 
-size_t elm_rnn_fit_workspace_bytes(int64_t N, int L, int m, int h_in_workspace) {
+size_t elm_rnn_fit_workspace_bytes(int cell, int64_t N, int Q, int d, int L, int m, int h_in_workspace) {
     const size_t s = elm_rnn_solve_workspace_bytes(N, L, m);
-    if (s == 0) return 0;
-    return s + (h_in_workspace ? (((size_t)N * L * sizeof(float) + 255) & ~(size_t)255) : 0);
+    if (s == 0 || check_dims(cell, Q, d, L, m) != ELM_OK) return 0;
+    return s + (h_in_workspace ? (((size_t)N * L * sizeof(float) + 255) & ~(size_t)255) : 0) +
+           hidden_scratch_bytes(cell, N, Q, d, L);
 }
 
 int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T, int64_t N,
-                int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init, void* workspace,
-                size_t workspace_bytes, void* hip_stream, float* H_out, float* beta_out,
+                int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init, int refine,
+                void* workspace, size_t workspace_bytes, void* hip_stream, float* H_out, float* beta_out,
                 double* beta64_out, elm_rnn_stats* stats, elm_rnn_model** model_out) {
     if (X == nullptr || T == nullptr || beta_out == nullptr || model_out == nullptr) return ELM_EINVAL;
-    if (N < 1 || N < L || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
+    if (N < 1 || N < L || ldx_n < 0 || ldx_q < 0 || refine < -1 || refine > 4) return ELM_EINVAL;
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
-    const size_t need = elm_rnn_fit_workspace_bytes(N, L, m, H_out == nullptr);
+    const size_t need = elm_rnn_fit_workspace_bytes(cell, N, Q, d, L, m, H_out == nullptr);
+    if (need == 0) return ELM_EUNSUPPORTED;
     if (workspace == nullptr || workspace_bytes < need) return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     elm_rnn_model* mdl = nullptr;
-    rc = elm_rnn_model_create(cell, Q, d, L, m, seed, init, &mdl);
+    rc = create_model(cell, Q, d, L, m, seed, init, stream, &mdl);
     if (rc != ELM_OK) return rc;
 
+    // workspace: [solve area][H when the caller gave no H_out][stage-1 scratch]
     const size_t solve_bytes = elm_rnn_solve_workspace_bytes(N, L, m);
+    const size_t h_bytes = H_out ? 0 : (((size_t)N * L * sizeof(float) + 255) & ~(size_t)255);
     float* H = H_out ? H_out : reinterpret_cast<float*>(static_cast<char*>(workspace) + solve_bytes);
+    void* scratch = static_cast<char*>(workspace) + solve_bytes + h_bytes;
 
     EventPair ev;
     hipError_t e = ev.create();
     if (e == hipSuccess) e = hipEventRecord(ev.a, stream);
     if (e == hipSuccess)
-        e = run_hidden(mdl, X, ldx_n, ldx_q, N, Q, nullptr, nullptr, H, nullptr, stream);
+        e = run_hidden(mdl, X, ldx_n, ldx_q, N, Q, nullptr, nullptr, H, nullptr, scratch, stream);
     if (e == hipSuccess) e = hipEventRecord(ev.b, stream);
     if (e != hipSuccess) {
         set_hip_error(e, "hidden-matrix stage");
@@ -456,7 +512,7 @@ int elm_rnn_fit(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const fl
     }
     // stage 2 is timed from the end of stage 1; the hidden time is read after the final sync
     elm_rnn_stats local{};
-    rc = run_solve(H, T, N, L, m, 2, beta_out, beta64_out, &local, workspace, solve_bytes, stream, 0.0,
+    rc = run_solve(H, T, N, L, m, refine, beta_out, beta64_out, &local, workspace, solve_bytes, stream, 0.0,
                    ev.b);
     if (rc != ELM_OK && rc != ELM_ERANK) {
         elm_rnn_free(mdl);
@@ -497,11 +553,7 @@ static int64_t streamed_chunk(int64_t N, int L, int64_t chunk_rows) {
 // level-0 R factors the in-kernel hand-off may ask for: two work-groups per compute unit for the layers of at
 // most 256 units, one above; 256 compute units assumed when none is visible (sizes are asked for up front)
 static int streamed_fused_groups_bound(int L) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-        cus = 256;
-    const int64_t g = (int64_t)(L <= 256 ? 2 : 1) * cus;
+    const int64_t g = (int64_t)(L <= 256 ? 2 : 1) * device_compute_units();
     return (int)(g > 1024 ? 1024 : g);
 }
 
@@ -512,15 +564,12 @@ static size_t streamed_plan_bytes(int64_t N, int L, int m) {
     return a > b ? a : b;
 }
 
-size_t elm_rnn_fit_streamed_workspace_bytes(int64_t N, int L, int m, int64_t chunk_rows) {
-    if (elm_rnn_solve_workspace_bytes(N, L, m) == 0) return 0;
-    return streamed_plan_bytes(N, L, m) +
-           (((size_t)streamed_chunk(N, L, chunk_rows) * L * sizeof(float) + 255) & ~(size_t)255);
+size_t elm_rnn_fit_streamed_workspace_bytes(int cell, int64_t N, int Q, int d, int L, int m, int64_t chunk_rows) {
+    if (elm_rnn_solve_workspace_bytes(N, L, m) == 0 || check_dims(cell, Q, d, L, m) != ELM_OK) return 0;
+    const int64_t chunk = streamed_chunk(N, L, chunk_rows);
+    return streamed_plan_bytes(N, L, m) + (((size_t)chunk * L * sizeof(float) + 255) & ~(size_t)255) +
+           hidden_scratch_bytes(cell, chunk, Q, d, L);
 }
-
-// max|R_jj| / min|R_jj| above which the automatic mode of the streamed fit refines beta: the normal-equation
-// residual of the unrefined float32 solution grows like 1e-8 .. 6e-8 times this ratio
-static constexpr double kStreamedRefineRatio = 30.0;
 
 int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q, const float* T, int64_t N,
                          int Q, int d, int L, int m, uint64_t seed, const elm_rnn_init* init,
@@ -531,15 +580,17 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
     if (N < 1 || N < L || refine < -1 || refine > 4 || ldx_n < 0 || ldx_q < 0 || chunk_rows < -1) return ELM_EINVAL;
     int rc = check_dims(cell, Q, d, L, m);
     if (rc != ELM_OK) return rc;
-    const size_t need = elm_rnn_fit_streamed_workspace_bytes(N, L, m, chunk_rows);
+    const size_t need = elm_rnn_fit_streamed_workspace_bytes(cell, N, Q, d, L, m, chunk_rows);
     if (need == 0) return ELM_EUNSUPPORTED;
     if (workspace == nullptr || workspace_bytes < need) return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // workspace: [solve area][one chunk of H][stage-1 scratch for a chunk of rows]
     const int64_t chunk = streamed_chunk(N, L, chunk_rows);
     float* Hc = reinterpret_cast<float*>(static_cast<char*>(workspace) + streamed_plan_bytes(N, L, m));
+    void* scratch = reinterpret_cast<char*>(Hc) + (((size_t)chunk * L * sizeof(float) + 255) & ~(size_t)255);
 
     elm_rnn_model* mdl = nullptr;
-    rc = elm_rnn_model_create(cell, Q, d, L, m, seed, init, &mdl);
+    rc = create_model(cell, Q, d, L, m, seed, init, stream, &mdl);
     if (rc != ELM_OK) return rc;
 
     // In-kernel hand-off (the tile goes from LDS into the fold) where stage 1 has such a variant: forced by
@@ -556,7 +607,7 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
         return ELM_EUNSUPPORTED;
     }
     const bool fuse = fused_groups > 0 && fused_groups <= streamed_fused_groups_bound(L) &&
-                      (chunk_rows == -1 || (chunk_rows == 0 && per_cu == 1 && fused_groups >= 256));
+                      (chunk_rows == -1 || (chunk_rows == 0 && per_cu == 1 && fused_groups >= device_compute_units()));
     const SolvePlan plan = fuse ? make_solve_plan(N, L, m, fused_groups) : make_solve_plan(N, L, m);
     const double* small = reinterpret_cast<const double*>(static_cast<const char*>(workspace) + plan.off_small);
 
@@ -597,7 +648,7 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
             hipError_t e = (s1.used >= 128) ? s1.collect(stream) : hipSuccess;
             if (e == hipSuccess) e = s1.mark(stream);
             if (e == hipSuccess)
-                e = run_hidden(mdl, X + r0 * ldx_n, ldx_n, ldx_q, rows, Q, nullptr, nullptr, Hc, nullptr, stream);
+                e = run_hidden(mdl, X + r0 * ldx_n, ldx_n, ldx_q, rows, Q, nullptr, nullptr, Hc, nullptr, scratch, stream);
             if (e == hipSuccess) e = s1.mark(stream);
             if (e == hipSuccess) e = consume(T + r0 * m, rows, r0 > 0);
             if (e != hipSuccess) return e;
@@ -632,7 +683,7 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
         e = hipMemcpyAsync(sc, small + SmallArea::scal(L, m), sizeof sc, hipMemcpyDeviceToHost, stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);
         if (e != hipSuccess) return fail(e, "streamed fit: condition read-back");
-        updates = (sc[6] == 0.0 && sc[5] > kStreamedRefineRatio * sc[4]) ? 2 : 0;
+        updates = (sc[6] == 0.0 && sc[5] > kAutoRefineRatio * sc[4]) ? 2 : 0;
     }
     // every refinement step, and the statistics of the final beta, need H again: it is recomputed
     for (int it = 0; updates > 0 && it <= updates; ++it) {
@@ -679,9 +730,14 @@ int elm_rnn_fit_streamed(int cell, const float* X, int64_t ldx_n, int64_t ldx_q,
     return sc[6] != 0.0 ? ELM_ERANK : ELM_OK;
 }
 
-size_t elm_rnn_predict_workspace_bytes(int64_t N, int L) {
-    if (N < 1 || L < 1) return 0;
-    return ((size_t)N * L * sizeof(float) + 255) & ~(size_t)255;
+// H for `rows` rows followed by the stage-1 scratch for as many
+static size_t predict_bytes(const elm_rnn_model* model, int64_t rows) {
+    return (((size_t)rows * model->L * sizeof(float) + 255) & ~(size_t)255) + hidden_scratch_bytes(model, rows);
+}
+
+size_t elm_rnn_predict_workspace_bytes(const elm_rnn_model* model, int64_t N) {
+    if (model == nullptr || N < 1) return 0;
+    return predict_bytes(model, N);
 }
 
 int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, int64_t ldx_q,
@@ -689,16 +745,25 @@ int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, i
                     void* hip_stream) {
     if (model == nullptr || X == nullptr || Y_out == nullptr || N < 1 || ldx_n < 0 || ldx_q < 0) return ELM_EINVAL;
     if (workspace == nullptr) return ELM_EWORKSPACE;
-    // H is produced and consumed in chunks of as many rows as the workspace holds (whole groups of 256)
-    int64_t chunk = (int64_t)(workspace_bytes / ((size_t)model->L * sizeof(float)));
-    if (chunk < N) chunk = chunk / 256 * 256;
+    // H is produced and consumed in chunks of as many rows as the workspace holds (whole groups of 256);
+    // predict_bytes() never decreases with the rows, so the largest chunk that fits is found by bisection
+    int64_t chunk = N;
+    if (predict_bytes(model, N) > workspace_bytes) {
+        int64_t lo = 0, hi = (N + 255) / 256;               // in units of 256 rows: lo fits (or is 0), hi does not
+        while (hi - lo > 1) {
+            const int64_t mid = lo + (hi - lo) / 2;
+            if (predict_bytes(model, mid * 256) <= workspace_bytes) lo = mid; else hi = mid;
+        }
+        chunk = lo * 256;
+    }
     if (chunk < 1) return ELM_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float* H = static_cast<float*>(workspace);
+    void* scratch = static_cast<char*>(workspace) + (((size_t)chunk * model->L * sizeof(float) + 255) & ~(size_t)255);
     for (int64_t r0 = 0; r0 < N; r0 += chunk) {
         const int64_t rows = (N - r0 < chunk) ? N - r0 : chunk;
         ELM_HIP_TRY(run_hidden(model, X + r0 * ldx_n, ldx_n, ldx_q, rows, model->Q, nullptr, nullptr, H, nullptr,
-                               stream));
+                               scratch, stream));
         ELM_HIP_TRY(launch_predict_gemv(H, model->dBeta, rows, model->L, model->m, Y_out + r0 * model->m, stream));
     }
     return ELM_OK;

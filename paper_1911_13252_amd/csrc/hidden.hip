@@ -61,7 +61,7 @@ hipError_t launch_cell(int ms, int nch, const HiddenArgs& a, int64_t N, size_t l
     // one column chunk (L <= 128; two chunks for Elman and GRU) also run 32-row blocks per wave: those
     // variants fit 256 registers, so two or more waves share a SIMD
     const bool two_waves = nch == 1 || (nch == 2 && CELL != ELM_CELL_LSTM);
-    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < 256 || two_waves)) ms = 1;
+    if (ms == 2 && ((N + 64 * wr - 1) / (64 * wr) < device_compute_units() || two_waves)) ms = 1;
     if (wr > 1) {
         const int Sw = 32 * ms * wr;
         const int64_t tiles = (N + Sw - 1) / Sw;

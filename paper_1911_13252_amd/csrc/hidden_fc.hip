@@ -480,20 +480,29 @@ bool fc_step_layout(int Q, int d, int L, FcStepLayout* out) {
     // 65,536 rows are two full rounds of 64-row work-groups at two per compute unit; larger passes measured
     // slower (100,096 rows: three rounds and a fraction), and so did 49,152 (one and a half)
     lay.chunk_rows = rows < 256 ? 256 : rows > 65536 ? 65536 : rows;
-    lay.hist_floats = (size_t)lay.chunk_rows * lay.ring * lay.Lk;
     // 97 to 112 units would take 7 units: measured 1.6 % faster than four 32-column blocks, with 22 registers
     // spilled; those layers keep the 32-column kernel
     lay.NU = (L > 64 && L <= 96) ? (L + 15) / 16 : 0;
     lay.floats16 = (size_t)lay.NU * KGpad * 128;
+    if (out != nullptr) *out = lay;
+    return true;
+}
+
+FcScratch fc_scratch(const FcStepLayout& lay, int64_t N) {
+    FcScratch sc{};
+    const int64_t n256 = (N + 255) / 256 * 256;
+    sc.pass_rows = n256 < lay.chunk_rows ? n256 : lay.chunk_rows;
+    sc.hist_floats = (size_t)sc.pass_rows * lay.ring * lay.Lk;
     // scratch sums: a block of steps carried for layers of at most 64 units ([row][128]); eight slices of raw
     // sums for launches of fewer than 128 work-groups ([slice][row][32 nJB])
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
-    const int64_t few_rows = (int64_t)128 * 32 * (4 / cw) < lay.chunk_rows ? (int64_t)128 * 32 * (4 / cw) : lay.chunk_rows;
-    const size_t carried = lay.nJB <= 2 ? (size_t)lay.chunk_rows * 128 : 0;
+    const int64_t few_rows = (int64_t)128 * 32 * (4 / cw) < sc.pass_rows ? (int64_t)128 * 32 * (4 / cw) : sc.pass_rows;
+    const size_t carried = lay.nJB <= 2 ? (size_t)sc.pass_rows * 128 : 0;
     const size_t split = (size_t)8 * few_rows * 32 * lay.nJB;
-    lay.sums_floats = carried > split ? carried : split;
-    if (out != nullptr) *out = lay;
-    return true;
+    sc.sums_floats = carried > split ? carried : split;
+    sc.off_sums = (sc.hist_floats * sizeof(float) + 255) & ~(size_t)255;
+    sc.bytes = (sc.off_sums + sc.sums_floats * sizeof(float) + 255) & ~(size_t)255;
+    return sc;
 }
 
 // Stack rows: slot s = 0 .. ring-1 holds lag ring - s (Lk rows, those beyond L zero), then W, b, zeros.
@@ -548,10 +557,13 @@ void pack_weights_fc_rows(const FcStepLayout& lay, const float* W, const float* 
                 }
 }
 
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, float* hist,
-                                  float* sums, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, void* scratch,
+                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream) {
-    if (Q_run < 1 || Q_run > lay.Q || N < 1) return hipErrorInvalidValue;
+    if (Q_run < 1 || Q_run > lay.Q || N < 1 || scratch == nullptr) return hipErrorInvalidValue;
+    const FcScratch scr = fc_scratch(lay, N);
+    float* hist = static_cast<float*>(scratch);
+    float* sums = reinterpret_cast<float*>(static_cast<char*>(scratch) + scr.off_sums);
     const int cw = lay.nJB >= 3 ? 4 : lay.nJB;
     const int ycount = (lay.nJB + cw - 1) / cw;
     const int ldsums = 128;                    // carried sums of a block of steps: [row][B][32 nJB]
@@ -574,7 +586,7 @@ hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, cons
         // a pass of few rows (long windows: the history of 1,000 rows can be 1 GB) leaves compute units idle:
         // its launches split the contraction over up to 8 slices of the operand chunks instead
         const int64_t wgs = (rows + S1 - 1) / S1 * ycount;
-        const bool few = sums != nullptr && wgs < 128 && (size_t)8 * rows * ldp <= lay.sums_floats;
+        const bool few = sums != nullptr && wgs < 128 && (size_t)8 * rows * ldp <= scr.sums_floats;
         // steps per block: the waves that a layer of one or two column blocks leaves free take further steps
         const int B = (sums != nullptr && lay.nJB <= 2 && !few) ? 4 / lay.nJB : 1;
         if (Wp16 != nullptr && lay.NU > 0 && (rows + 127) / 128 >= 256) {       // every compute unit gets a tile

@@ -32,7 +32,7 @@ void pack_weights_fc(const PackedLayout& lay, const float* W, const float* A, co
 constexpr int kFcMaxK = 1272;      // contraction rows a 32-sample tile of the multi-lag cell can hold in LDS
 
 // ---- the fully connected multi-lag cell when the history of a window does not fit LDS: a launch per step,
-// the past states of a chunk of rows kept in a device buffer the model owns
+// the past states of a pass of rows kept in scratch memory that the caller's workspace provides
 struct FcStepLayout {
     int Q, d, L;
     int ring;             // history slots per row (Q - 1, at least 1)
@@ -41,9 +41,7 @@ struct FcStepLayout {
     int KGtot;            // k-groups of 8 rows in the stack [A_{Q-1}; ...; A_1; W; b]
     int KGpad;            // ... plus the zero groups the contraction may run or look into
     size_t floats;        // packed stack: nJB * KGpad * 256
-    int64_t chunk_rows;   // rows the history buffer holds (a multiple of 256, at most 65,536)
-    size_t hist_floats;   // chunk_rows * ring * Lk
-    size_t sums_floats;   // scratch for carried and split sums
+    int64_t chunk_rows;   // most rows a pass takes (a multiple of 256, at most 65,536)
     int NU;               // 16-column units of the row-split kernel (layers of 65 to 96 units), else 0
     size_t floats16;      // the stack packed per unit: NU * KGpad * 128
 };
@@ -51,10 +49,20 @@ struct FcStepLayout {
 bool fc_step_layout(int Q, int d, int L, FcStepLayout* out);
 void pack_weights_fc_steps(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
 void pack_weights_fc_rows(const FcStepLayout& lay, const float* W, const float* A, const float* b, float* out);
-// hist: lay.hist_floats, sums: lay.sums_floats of model-owned scratch
+// Scratch of one call over N rows: the history of a pass ([slot][row][Lk]) followed by the carried / split
+// sums.  bytes does not decrease when N grows, so the scratch for a chunk of rows also serves shorter ones.
+struct FcScratch {
+    int64_t pass_rows;    // min(N rounded up to 256, lay.chunk_rows)
+    size_t hist_floats;   // pass_rows * ring * Lk
+    size_t sums_floats;
+    size_t off_sums;      // byte offset of the sums (256-byte aligned)
+    size_t bytes;
+};
+FcScratch fc_scratch(const FcStepLayout& lay, int64_t N);
+// scratch: fc_scratch(lay, N).bytes of device memory, contents destroyed
 // Wp16: the per-unit packing (lay.floats16) where lay.NU > 0, else null
-hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, float* hist,
-                                  float* sums, const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
+hipError_t launch_hidden_fc_steps(const FcStepLayout& lay, const float* Wp, const float* Wp16, void* scratch,
+                                  const float* X, int64_t ldx_n, int64_t ldx_q, int64_t N, int Q_run, float* H,
                                   hipStream_t stream);
 
 hipError_t launch_hidden(const PackedLayout& lay, const float* Wp, const float* X, int64_t ldx_n,
@@ -70,8 +78,11 @@ hipError_t launch_hidden_tiny(int cell, int d, int L, const float* Wp, const flo
                               int64_t N, int Q_run, const float* h0, const float* c0, float* H, float* C,
                               hipStream_t stream);
 
-// Spectral radius of a row-major n x n float64 host matrix, computed on the current device.
-hipError_t spectral_radius_device(const double* A, int n, double* rho_out);
+// Spectral radius of a row-major n x n float64 host matrix, computed on the current device; every launch
+// and copy goes to `stream`, which is synchronised before the function returns.
+hipError_t spectral_radius_device(const double* A, int n, double* rho_out, hipStream_t stream);
+// compute units of the current device (256 when the query fails: the launch heuristics only need a scale)
+int device_compute_units();
 
 // ---- fast contraction mode (fp16 hi/lo split of the recurrent part, bf16 x 3 split of the input part)
 struct SplitLayout {
@@ -143,6 +154,12 @@ hipError_t launch_export_beta(const SolvePlan& plan, void* ws, float* beta32, do
 hipError_t launch_predict_gemv(const float* H, const double* beta64, int64_t N, int L, int m,
                                float* Y, hipStream_t stream);
 
+// Stage 2 on `stream` with a plan the caller made; ws (device) holds plan.bytes.  Arguments as elm_rnn_solve;
+// hidden_done (nullable) is an event recorded when stage 1 ended, from which the solve time is then measured.
+int run_solve_with_plan(const SolvePlan& plan, const float* H, const float* T, int refine, float* beta_out,
+                        double* beta64_out, elm_rnn_stats* stats, void* ws, hipStream_t stream,
+                        double hidden_ms, hipEvent_t hidden_done);
+
 // layout of the "small" double area of the solve workspace
 struct SmallArea {
     static constexpr int BETA = 0;                 // L*m      current beta (float64)
@@ -153,6 +170,7 @@ struct SmallArea {
 };
 
 void set_hip_error(hipError_t e, const char* where);
+void set_error_text(const char* text);      // what elm_rnn_last_hip_error() then returns
 
 }  // namespace elm
 

@@ -82,7 +82,14 @@ extern "C" int elm_rnn_probe_ceilings(double* mfma_f32_tflops, double* mfma_f16_
     ELM_HIP_TRY(hipMemcpyAsync(in, seeds.data(), seeds.size() * sizeof(float), hipMemcpyHostToDevice, stream));
     hipEvent_t a = nullptr, b = nullptr;
     ELM_HIP_TRY(hipEventCreate(&a));
-    ELM_HIP_TRY(hipEventCreate(&b));
+    {
+        const hipError_t eb = hipEventCreate(&b);
+        if (eb != hipSuccess) {
+            (void)hipEventDestroy(a);
+            set_hip_error(eb, "hipEventCreate");
+            return ELM_EHIP;
+        }
+    }
     auto timed = [&](auto&& launch, float* ms) -> hipError_t {
         launch();                                               // warm-up
         hipError_t e = hipEventRecord(a, stream);

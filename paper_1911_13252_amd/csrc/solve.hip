@@ -1,6 +1,6 @@
-// Stage 2b: from the R factor of [H | T] to beta (the paper's section "Computing beta":
-// "beta would be the solution of R beta = z by back substitution"), plus float64-residual
-// iterative refinement of beta and the prediction product Y = H beta (the paper's output equation
+// Stage 2b: from the R factor of [H | T] to beta (the paper's section "Computing beta": the triangular
+// back-solve R11 beta = R12, i.e. R beta = z with z = Q^T Y), plus float64-residual iterative
+// refinement of beta and the prediction product Y = H beta (the paper's output equation
 // y_hat = sum_i beta_i f_i).
 //
 // R = [R11 R12; 0 R22] (np x np float32, upper triangular).  beta0 = R11^{-1} R12 in float64

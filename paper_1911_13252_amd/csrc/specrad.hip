@@ -105,7 +105,7 @@ struct DeviceBuffers {
 
 }  // namespace
 
-hipError_t spectral_radius_device(const double* A, int n, double* rho_out) {
+hipError_t spectral_radius_device(const double* A, int n, double* rho_out, hipStream_t stream) {
     constexpr int kMaxSquarings = 48;    // 2^-48 |log ||B^2||| is below double rounding of log rho
     constexpr int kBatch = 16;           // squarings enqueued between two looks at the norms
     double nf2 = 0.0;
@@ -118,10 +118,17 @@ hipError_t spectral_radius_device(const double* A, int n, double* rho_out) {
     const int tiles = (n + TS - 1) / TS, nblocks = tiles * tiles;
     DeviceBuffers d;
     hipError_t e = d.allocate((size_t)n * n, (size_t)nblocks, kMaxSquarings + 1);
-    if (e == hipSuccess) e = hipMemcpy(d.m[0], A, (size_t)n * n * sizeof(double), hipMemcpyHostToDevice);
+    // every copy and launch below is on the caller's stream; the host buffers of the uploads stay alive until
+    // the first read-back has synchronised that stream
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(d.m[0], A, (size_t)n * n * sizeof(double), hipMemcpyHostToDevice, stream);
     // the first squaring reads ||A||_F^2 as a single partial sum
-    if (e == hipSuccess) e = hipMemcpy(d.partial + nblocks, &nf2, sizeof(double), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return e;
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(d.partial + nblocks, &nf2, sizeof(double), hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(stream);       // nothing may still read A or nf2 after the return
+        return e;
+    }
 
     double norms[kMaxSquarings + 1];
     double log_rho = std::log(nf), w = 1.0, prev = -1.0;
@@ -131,15 +138,18 @@ hipError_t spectral_radius_device(const double* A, int n, double* rho_out) {
         // other set (the very first one reads the single entry ||A||_F^2 placed there by the host); it
         // stores the norm of its input, so one norm kernel per batch supplies the last output's norm
         for (int it = base; it < base + kBatch; ++it) {
-            hipLaunchKernelGGL(square_kernel, dim3(tiles, tiles), dim3(256), 0, nullptr, d.m[it & 1],
+            hipLaunchKernelGGL(square_kernel, dim3(tiles, tiles), dim3(256), 0, stream, d.m[it & 1],
                                d.m[(it + 1) & 1], n, d.partial + ((it + 1) & 1) * nblocks, it == 0 ? 1 : nblocks,
                                d.partial + (it & 1) * nblocks, d.norms + it);
         }
-        hipLaunchKernelGGL(norm_kernel, dim3(1), dim3(64), 0, nullptr, d.partial + ((base + kBatch - 1) & 1) * nblocks,
+        hipLaunchKernelGGL(norm_kernel, dim3(1), dim3(64), 0, stream, d.partial + ((base + kBatch - 1) & 1) * nblocks,
                            nblocks, d.norms + base + kBatch);
         e = hipGetLastError();
         if (e == hipSuccess)
-            e = hipMemcpy(norms + base + 1, d.norms + base + 1, kBatch * sizeof(double), hipMemcpyDeviceToHost);
+            e = hipMemcpyAsync(norms + base + 1, d.norms + base + 1, kBatch * sizeof(double), hipMemcpyDeviceToHost,
+                               stream);
+        const hipError_t es = hipStreamSynchronize(stream);     // also on failure: the buffers are freed on return
+        if (e == hipSuccess) e = es;
         if (e != hipSuccess) return e;
         for (int it = base; it < base + kBatch; ++it) {
             const double nc = norms[it + 1];

@@ -153,8 +153,10 @@ SolvePlan make_solve_plan(int64_t N, int L, int m, int level0_groups) {
     int64_t g0 = (nblocks + 3) / 4;
     if (g0 < 1) g0 = 1;
     // one work-group per compute unit; three where the width is a single panel (np == 32: that kernel
-    // needs few registers and little LDS, and its Householder chains then overlap)
-    const int64_t cap = (pl.np == 32) ? 768 : 256;
+    // needs few registers and little LDS, and its Householder chains then overlap); at most 1024 R factors
+    const int cus = device_compute_units();
+    int64_t cap = (pl.np == 32) ? 3 * (int64_t)cus : cus;
+    if (cap > 1024) cap = 1024;
     if (g0 > cap) g0 = cap;
     if (level0_groups > 0) g0 = level0_groups;      // the fused stage-1 kernel brings its own grid
     pl.levels = 0;

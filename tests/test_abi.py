@@ -49,6 +49,21 @@ def test_host_only_entry_points(lib):
     assert elm.fit_streamed_workspace_bytes(1000, 16, 1) >= elm.fit_workspace_bytes(1000, 16, 1, True)
     assert elm.fit_streamed_workspace_bytes(1000, 16, 1) - elm.fit_workspace_bytes(1000, 16, 1, True) <= 1024 * 32 * 32 * 4 * 2
     assert elm.fit_streamed_workspace_bytes(1000, 513, 1, 0) == 0
+    # stage-1 scratch: none for the cells whose per-step states stay on chip; for the multi-lag cell beyond
+    # its on-chip limit the history of a pass of rows ([Q-1 slots][rows rounded to 256][L rounded to 8]
+    # floats, at most 65,536 rows) plus carried sums; never smaller for more rows; part of the fit sizes
+    for cell in ("elman", "lstm", "gru", "elman_diag"):
+        assert elm.hidden_workspace_bytes(cell, 100_000, 50, 4, 100) == 0
+    assert elm.hidden_workspace_bytes("fc_multilag", 100_000, 10, 4, 100) == 0        # history ring in LDS
+    h = [elm.hidden_workspace_bytes("fc_multilag", n, 50, 4, 100) for n in (1, 256, 257, 3000, 65536, 65537, 700_000)]
+    assert h[0] == h[1] and all(b >= a for a, b in zip(h, h[1:])) and h[4] == h[5] == h[6]
+    assert 49 * 256 * 104 * 4 <= h[0] < 49 * 256 * 104 * 4 + (2 << 20)
+    assert 49 * 65536 * 104 * 4 <= h[-1] < (2 << 30)
+    assert (elm.fit_workspace_bytes(3000, 100, 1, False, "fc_multilag", 50, 4)
+            == elm.fit_workspace_bytes(3000, 100, 1, False) + h[3])
+    assert (elm.fit_streamed_workspace_bytes(700_000, 100, 1, 4096, "fc_multilag", 50, 4)
+            == elm.fit_streamed_workspace_bytes(700_000, 100, 1, 4096) + elm.hidden_workspace_bytes("fc_multilag", 4096, 50, 4, 100))
+    assert elm.hidden_workspace_bytes("fc_multilag", 1000, 50, 4, 513) == 0           # unsupported width
 
 
 def test_no_cpu_fallback_and_no_oracle_in_the_product():

@@ -52,10 +52,10 @@ def test_hidden_and_model_argument_errors(elm):
     lib = elm.load_library()
     # Q_run < 1 and N < 1 are invalid arguments (no launch happens)
     H = torch.empty((5, 8), device="cuda")
-    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 8, 2, 5, 0, None, None, H.data_ptr(), None, None) == -1
-    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 8, 2, 0, 4, None, None, H.data_ptr(), None, None) == -1
-    assert lib.elm_rnn_hidden(model._h, None, 8, 2, 5, 4, None, None, H.data_ptr(), None, None) == -1
-    assert lib.elm_rnn_hidden(None, X.data_ptr(), 8, 2, 5, 4, None, None, H.data_ptr(), None, None) == -1
+    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 8, 2, 5, 0, None, None, H.data_ptr(), None, None, 0, None) == -1
+    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 8, 2, 0, 4, None, None, H.data_ptr(), None, None, 0, None) == -1
+    assert lib.elm_rnn_hidden(model._h, None, 8, 2, 5, 4, None, None, H.data_ptr(), None, None, 0, None) == -1
+    assert lib.elm_rnn_hidden(None, X.data_ptr(), 8, 2, 5, 4, None, None, H.data_ptr(), None, None, 0, None) == -1
     model.close()
     with pytest.raises(elm.ElmRnnError) as ei:
         elm.Model.create("lstm", 4, 2, 513, 1, seed=1, w_scale=0.1)

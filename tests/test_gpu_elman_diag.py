@@ -129,7 +129,7 @@ def test_argument_errors(elm):
     lib = elm.load_library()
     H = torch.empty((5, 8), device="cuda")
     # more steps than the model has lag weights for
-    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 12, 2, 5, 7, None, None, H.data_ptr(), None, None) == -1
+    assert lib.elm_rnn_hidden(model._h, X.data_ptr(), 12, 2, 5, 7, None, None, H.data_ptr(), None, None, 0, None) == -1
     model.close()
     with pytest.raises(elm.ElmRnnError) as ei:
         elm.Model.create("elman_diag", 4097, 1, 4, 1, seed=1)
