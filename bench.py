@@ -43,6 +43,10 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3   # MI355X fp32 vector peak (256 CUs x 4 SIMDs x
 # Infinity Cache, which never reach HBM.
 MEASURED_TRAFFIC_BYTES = {"cfg5": 922.8e9 + 39.1e9}   # profiles/hidden_kernel_cfg5_pmc.txt (L2-boundary traffic)
 MEASURED_TRAFFIC_SPLIT_BYTES = {"cfg5": 1283.1e9 + 413.7e9}   # profiles/fit_cfg5_split16_kernel_trace_and_pmc.txt
+TRAFFIC_SOURCE = ("profiles/hidden_kernel_cfg5_pmc.txt: stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE figure of the "
+                  "same launch, not measured by this run")
+TRAFFIC_SPLIT_SOURCE = ("profiles/fit_cfg5_split16_kernel_trace_and_pmc.txt: stored rocprofv3 --pmc figure, not "
+                        "measured by this run")
 
 
 def stage1_flops(cfg) -> float:
@@ -54,6 +58,72 @@ def stage1_flops(cfg) -> float:
     if cfg.cell == "fc_multilag":      # step t contracts (t - 1) L + d columns
         return 2.0 * cfg.L * (cfg.L * cfg.Q * (cfg.Q - 1) / 2 + cfg.Q * cfg.d) * cfg.N
     return 2.0 * cfg.Q * GATES[cfg.cell] * cfg.L * (cfg.L + cfg.d) * cfg.N
+
+
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
+
+
+def stage2_work(cfg):
+    """Algorithmic work of the solve on an N x n matrix, n = L + m: Householder flops 2 N n^2 - 2/3 n^3 and
+    4 N n bytes (the rows of [H | T] read once)."""
+    n = cfg.L + cfg.m
+    return 2.0 * cfg.N * n * n - (2.0 / 3.0) * n ** 3, 4.0 * cfg.N * n
+
+
+def stage2_roofline(cfg, solve_ms):
+    """Stage 2 against both of its ceilings (the larger of the two times bounds it)."""
+    flops, nbytes = stage2_work(cfg)
+    tf = flops / (solve_ms * 1e-3) / 1e12
+    gbs = nbytes / (solve_ms * 1e-3) / 1e9
+    t_roof_ms = 1e3 * max(flops / (PEAK_FP32_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9))
+    return {"kernel": "tsqr_fold_kernel + back-solve + refinement (stage 2)", "solve_ms": solve_ms,
+            "achieved_tflops": tf, "frac_of_fp32_mfma_peak": tf / PEAK_FP32_MFMA_TFLOPS,
+            "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS,
+            "roofline_ms": t_roof_ms, "frac_of_roofline": t_roof_ms / solve_ms}
+
+
+def measure_config(elm, torch, cfg, steps: int, cpu_rows: int) -> dict:
+    """One of the smaller benchmark configurations, float32 mode, materialised windows resident in HBM:
+    a warm-up fit and `steps` timed ones, per-stage times from the library's events on the launch stream."""
+    series = synthdata.make_series(cfg.N + cfg.Q, cfg.d, cfg.seed, cfg.ar_sigma).astype(np.float32)
+    sd = torch.from_numpy(series).cuda()
+    X = torch.as_strided(sd, (cfg.N, cfg.Q, cfg.d), (cfg.d, cfg.d, 1)).contiguous()
+    T = sd[cfg.Q:cfg.Q + cfg.N, :cfg.m].contiguous()
+    H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
+    ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False, cfg.cell, cfg.Q, cfg.d),
+                     dtype=torch.uint8, device="cuda")
+    kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
+              zero_bias=cfg.zero_bias, workspace=ws, H_out=H)
+
+    def one():
+        res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)
+        st = res.stats
+        res.model.close()
+        return st
+
+    one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats = [one() for _ in range(steps)]
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    hidden_ms = float(np.mean([s.t_hidden_ms for s in stats]))
+    solve_ms = float(np.mean([s.t_solve_ms for s in stats]))
+    tf = stage1_flops(cfg) / (hidden_ms * 1e-3) / 1e12
+    out = {"workload": f"{cfg.name}: {cfg.cell} ELM-RNN fit, N={cfg.N}, Q={cfg.Q}, d={cfg.d}, L={cfg.L}, m={cfg.m}, "
+                       "materialised windows resident in HBM",
+           "dtype": "f32", "steps": steps, "value": cfg.N / dt, "unit": "samples/s", "ms_per_step": 1e3 * dt,
+           "hidden_ms": hidden_ms, "solve_ms": solve_ms, "host_ms": 1e3 * dt - hidden_ms - solve_ms,
+           "hidden_samples_per_s": cfg.N / (hidden_ms * 1e-3), "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
+           "rmse": stats[-1].rmse, "ne_resid": stats[-1].ne_resid, "refine_iters": stats[-1].refine_iters,
+           "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                        "frac": tf / PEAK_FP32_MFMA_TFLOPS,
+                        "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"},
+           "stage2": stage2_roofline(cfg, solve_ms)}
+    del X, T, H, ws
+    if cpu_rows > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, cpu_rows)
+    return out
 
 
 def cpu_baseline(cfg, budget_rows: int):
@@ -86,7 +156,7 @@ def run_sweep(elm, torch, steps: int) -> dict:
 
     def timed_fit(cfg, X, T, mode):
         H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
-        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False, cfg.cell, cfg.Q, cfg.d), dtype=torch.uint8, device="cuda")
         kw = dict(w_scale=cfg.w_scale, spectral_radius=cfg.spectral_radius, forget_bias=cfg.forget_bias,
                   zero_bias=cfg.zero_bias, contraction=mode, workspace=ws, H_out=H, allow_rank_deficient=True)
         res = elm.fit(cfg.cell, X, T, cfg.L, cfg.seed, **kw)          # warm-up
@@ -192,6 +262,8 @@ def main() -> int:
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="streamed fit: 0 = library default, -1 = in-kernel hand-off, > 0 = rows per chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the extra measurements of the four smaller benchmark configurations")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceilings probe")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--n", type=int, default=0, help="override N (profiling runs only; the reported "
@@ -232,11 +304,11 @@ def main() -> int:
     if args.streamed:
         args.no_streamed = True
         H = None
-        ws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0)),
+        ws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0), cfg.cell, cfg.Q, cfg.d),
                          dtype=torch.uint8, device="cuda")
     else:
         H = torch.empty((cfg.N, cfg.L), dtype=torch.float32, device="cuda")
-        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, False, cfg.cell, cfg.Q, cfg.d), dtype=torch.uint8, device="cuda")
 
     def step(mode=args.contraction):
         if args.streamed:
@@ -259,6 +331,7 @@ def main() -> int:
             r = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                  "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                  "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                 "traffic_source": TRAFFIC_SOURCE if cfg.name in MEASURED_TRAFFIC_BYTES else None,
                  "kernel": "hidden_kernel (stage 1, fp32 MFMA 32x32x2)"}
             if cfg.cell == "fc_multilag" and (cfg.Q - 1) * cfg.L + cfg.d + 1 > 1272:
                 r["kernel"] = "fc_step_kernel (stage 1, one launch per step, fp32 MFMA 32x32x2)"
@@ -268,6 +341,7 @@ def main() -> int:
         return {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_MFMA_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_SPLIT_BYTES.get(cfg.name),
+                "traffic_source": TRAFFIC_SPLIT_SOURCE if cfg.name in MEASURED_TRAFFIC_SPLIT_BYTES else None,
                 "kernel": "hidden_split_kernel (stage 1, fp16 MFMA 32x32x16, 3 products per float32 product)",
                 "issued_over_algorithmic": 3.0 * (16 * ((cfg.L + 15) // 16) + 32) / (cfg.L + cfg.d),
                 "achieved_over_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
@@ -316,8 +390,10 @@ def main() -> int:
                    "solve_samples_per_s": cfg.N / (solve_ms * 1e-3),
                    "contraction": args.contraction, "streamed": bool(args.streamed),
                    "rmse": stats[-1].rmse,
-                   "ne_resid": None if np.isnan(stats[-1].ne_resid) else stats[-1].ne_resid},
+                   "ne_resid": None if np.isnan(stats[-1].ne_resid) else stats[-1].ne_resid,
+                   "refine_iters": stats[-1].refine_iters},
         "roofline": roofline(args.contraction, hidden_ms),
+        "stage2": stage2_roofline(cfg, solve_ms),
     }
     if (not args.no_fast_mode and args.contraction == "fp32" and cfg.d <= 15
             and cfg.cell in ("elman", "lstm", "gru")):
@@ -336,7 +412,7 @@ def main() -> int:
     if not args.no_streamed and args.contraction == "fp32":
         # the same fit with H produced and folded into the TSQR chunk by chunk (never stored)
         del H, ws
-        sws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0)),
+        sws = torch.empty(elm.fit_streamed_workspace_bytes(cfg.N, cfg.L, cfg.m, max(args.chunk_rows, 0), cfg.cell, cfg.Q, cfg.d),
                           dtype=torch.uint8, device="cuda")
 
         def sstep():
@@ -358,7 +434,7 @@ def main() -> int:
                                "solve_ms": float(np.mean([s.t_solve_ms for s in sstats])),
                                "refine_iters": sstats[-1].refine_iters, "rmse": sstats[-1].rmse,
                                "workspace_bytes": sws.numel(),
-                               "ordinary_fit_bytes": elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, True)}
+                               "ordinary_fit_bytes": elm.fit_workspace_bytes(cfg.N, cfg.L, cfg.m, True, cfg.cell, cfg.Q, cfg.d)}
     if not args.no_ceilings:
         # what this device sustains: register-resident matrix-instruction loops and a streaming copy
         torch.cuda.empty_cache()
@@ -370,11 +446,20 @@ def main() -> int:
                                                      else c["mfma_f16_tflops"])
         if "fast_mode" in out:
             out["fast_mode"]["roofline"]["frac_of_measured"] = out["fast_mode"]["roofline"]["achieved"] / c["mfma_f16_tflops"]
+    cpu_rows = {"cfg1": 2000, "cfg2": 100_000, "cfg3": 50_000, "cfg4": 16_384, "cfg5": 8192,
+                "paper_elman": 20_000, "paper_fc": 20_000, "paper_fc_q50": 20_000}
+    if not args.no_configs and cfg.name == "cfg5" and args.n == 0 and not args.streamed:
+        # the other four benchmark configurations (the headline fields above stay those of cfg5): at most
+        # three timed fits each; the oracle on all rows of cfg1 / cfg2 and on a slice of cfg3 / cfg4
+        del X, T
+        if not args.no_streamed and args.contraction == "fp32":
+            del sws
+        torch.cuda.empty_cache()
+        out["configs"] = [measure_config(elm, torch, synthdata.get_config(n), min(args.steps, 3),
+                                         0 if args.no_cpu_baseline else cpu_rows[n])
+                          for n in ("cfg1", "cfg2", "cfg3", "cfg4")]
     if not args.no_cpu_baseline:
-        rows = args.cpu_rows or {"cfg1": 2000, "cfg2": 100_000, "cfg3": 100_000, "cfg4": 16_384,
-                                 "cfg5": 8192, "paper_elman": 20_000, "paper_fc": 20_000,
-                                 "paper_fc_q50": 20_000}[cfg.name]
-        out["cpu_baseline"] = cpu_baseline(cfg, rows)
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_rows or cpu_rows[cfg.name])
     print(json.dumps(out))
     return 0
 
