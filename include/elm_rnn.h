@@ -193,6 +193,23 @@ int elm_rnn_solve(const float* H, const float* T, int64_t N, int L, int m, int r
                   float* beta_out, double* beta64_out, elm_rnn_stats* stats,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same solve for callers that cannot allocate device memory or obtain a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Everything elm_rnn_solve keeps
+ * in its workspace (R factors, partial sums, the small float64 area) lives in a static device array of
+ * ELM_RNN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from the load of the library until
+ * the process ends; the call allocates nothing (no hipMalloc / hipFree, no library that does).  Arguments and
+ * results as elm_rnn_solve.  Where the default number of level-0 R factors does not fit the array it is
+ * halved until it does (same result up to float32 rounding, longer run time: cfg-sized examples are
+ * 384 factors at L + m <= 160, 96 at 288, 48 at 544); ELM_EUNSUPPORTED, with the reason in
+ * elm_rnn_last_hip_error(), if even one R factor plus the 1024 x (L m + 2) float64 partial sums do not fit
+ * (e.g. L = 512 with m = 16).  All calls on one GPU share that GPU's array, which keeps the last call's
+ * contents (nothing in it needs clearing between calls): calls that overlap in time on one GPU race and
+ * must be serialised by the caller, e.g. by using one stream. */
+#define ELM_RNN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+size_t elm_rnn_solve_static_scratch_bytes(void);
+int elm_rnn_solve_static(const float* H, const float* T, int64_t N, int L, int m, int refine,
+                         float* beta_out, double* beta64_out, elm_rnn_stats* stats, void* hip_stream);
+
 /* ---- the whole fit -------------------------------------------------------------------------- */
 
 /* Workspace for elm_rnn_fit: the solve workspace, plus N*L floats when H_out is NULL, plus

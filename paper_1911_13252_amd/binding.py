@@ -17,7 +17,8 @@ DECLARED_SYMBOLS = (
     "elm_rnn_model_create", "elm_rnn_model_create_from_weights", "elm_rnn_get_weights",
     "elm_rnn_model_set_contraction", "elm_rnn_set_beta", "elm_rnn_free", "elm_rnn_hidden_workspace_bytes",
     "elm_rnn_hidden", "elm_rnn_solve_workspace_bytes",
-    "elm_rnn_solve", "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
+    "elm_rnn_solve", "elm_rnn_solve_static_scratch_bytes", "elm_rnn_solve_static",
+    "elm_rnn_fit_workspace_bytes", "elm_rnn_fit",
     "elm_rnn_fit_streamed_workspace_bytes", "elm_rnn_fit_streamed",
     "elm_rnn_predict_workspace_bytes", "elm_rnn_predict", "elm_rnn_strerror",
     "elm_rnn_last_hip_error", "elm_rnn_probe_workspace_bytes", "elm_rnn_probe_ceilings",
@@ -92,6 +93,9 @@ def load_library():
     lib.elm_rnn_solve_workspace_bytes.argtypes = [i64, C.c_int, C.c_int]
     lib.elm_rnn_solve_workspace_bytes.restype = sz
     lib.elm_rnn_solve.argtypes = [vp, vp, i64, C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(_Stats), vp, sz, vp]
+    lib.elm_rnn_solve_static_scratch_bytes.argtypes = []
+    lib.elm_rnn_solve_static_scratch_bytes.restype = sz
+    lib.elm_rnn_solve_static.argtypes = [vp, vp, i64, C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(_Stats), vp]
     lib.elm_rnn_fit_workspace_bytes.argtypes = [C.c_int, i64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     lib.elm_rnn_fit_workspace_bytes.restype = sz
     lib.elm_rnn_fit.argtypes = [C.c_int, vp, i64, i64, vp, i64, C.c_int, C.c_int, C.c_int, C.c_int, u64,
@@ -301,6 +305,28 @@ def solve(H, T, refine: int = 2, workspace=None, stream=None, allow_rank_deficie
     st = _Stats()
     rc = lib.elm_rnn_solve(H.data_ptr(), T.data_ptr(), N, L, m, refine, beta32.data_ptr(), beta64.data_ptr(),
                            C.byref(st), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(rc, allow_rank=allow_rank_deficient)
+    return beta32, beta64, _stats(st, rc == ELM_ERANK)
+
+
+def solve_static(H, T, refine: int = 2, stream=None, allow_rank_deficient: bool = False):
+    """elm_rnn_solve_static: elm_rnn_solve on the library's static device scratch array (the call itself
+    allocates nothing; the result tensors are made here before it)."""
+    import torch
+    lib = load_library()
+    _dev_f32(H, "H")
+    _dev_f32(T, "T")
+    if T.dim() == 1:
+        T = T[:, None]
+    if not (H.is_contiguous() and T.is_contiguous()):
+        raise ValueError("H and T must be contiguous")
+    N, L = H.shape
+    m = T.shape[1]
+    beta32 = torch.empty((L, m), dtype=torch.float32, device=H.device)
+    beta64 = torch.empty((L, m), dtype=torch.float64, device=H.device)
+    st = _Stats()
+    rc = lib.elm_rnn_solve_static(H.data_ptr(), T.data_ptr(), N, L, m, refine, beta32.data_ptr(), beta64.data_ptr(),
+                                  C.byref(st), _stream_ptr(stream))
     _check(rc, allow_rank=allow_rank_deficient)
     return beta32, beta64, _stats(st, rc == ELM_ERANK)
 

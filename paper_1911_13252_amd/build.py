@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libelmrnn.so")
-SOURCES = ("api.hip", "hidden.hip", "hidden_fused.hip", "hidden_split.hip", "hidden_tiny.hip", "hidden_diag.hip", "hidden_fc.hip", "specrad.hip", "tsqr.hip", "solve.hip", "probe.hip")
+SOURCES = ("api.hip", "hidden.hip", "hidden_fused.hip", "hidden_split.hip", "hidden_tiny.hip", "hidden_diag.hip", "hidden_fc.hip", "specrad.hip", "tsqr.hip", "solve.hip", "solve_static.hip", "probe.hip")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",

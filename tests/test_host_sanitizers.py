@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_1911_13252_amd", "csrc")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SOURCES = ("api.hip", "hidden.hip", "hidden_fused.hip", "hidden_split.hip", "hidden_tiny.hip", "hidden_diag.hip",
-           "hidden_fc.hip", "specrad.hip", "tsqr.hip", "solve.hip", "probe.hip")
+           "hidden_fc.hip", "specrad.hip", "tsqr.hip", "solve.hip", "solve_static.hip", "probe.hip")
 FLAGS = ["--offload-host-only", "-O1", "-g", "-std=c++17", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
          "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-Wno-unused-command-line-argument",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
