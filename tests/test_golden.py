@@ -50,3 +50,22 @@ def test_hip_path_matches_stored_values(elm, cell):
     np.testing.assert_allclose(res.beta64.cpu().numpy(), beta, rtol=0, atol=1e-4 * np.abs(beta).max())
     assert abs(res.stats.rmse - g["rmse"]) <= 1e-4 * g["rmse"]
     res.model.close()
+
+
+def test_chaos_rmse_file_is_consistent_with_the_yardstick_module():
+    """tests/golden/chaos_rmse.json (regenerated only by tests/golden/make_chaos_golden.py, 20 minutes of
+    oracle time): one float64 RMSE, one float32-yardstick RMSE per summation order and three perturbed
+    float64 RMSEs per configuration, all close to each other but not equal."""
+    import synthdata
+    from oracle import float32_yardstick as y32
+    with open(os.path.join(GOLDEN, "chaos_rmse.json")) as f:
+        g = json.load(f)
+    assert sorted(g) == ["cfg4", "cfg5"]
+    for name, v in g.items():
+        cfg = synthdata.get_config(name)
+        assert v["seed"] == cfg.seed and cfg.L + cfg.m <= v["N"] <= cfg.N
+        assert [tuple(x) for x in v["variants"]] == [tuple(x) for x in y32.VARIANTS]
+        assert len(v["rmse32"]) == len(y32.VARIANTS) and len(v["rmse64_perturbed"]) == 3
+        r64 = v["rmse64"]
+        dev = [abs(r - r64) / r64 for r in v["rmse32"] + v["rmse64_perturbed"]]
+        assert 0.0 < max(dev) < 5e-3 and 0.1 < r64 < 1.0

@@ -3,10 +3,11 @@
 Protocol (see the tolerance notes in test_gpu_hidden.py / test_gpu_solve.py):
   * cfg1, cfg2 (contractive Elman): H element-wise at full Q; solve stage-isolated on the GPU's H;
   * cfg3..cfg5 (LSTM / GRU at scales where float32 rounding is amplified over the full Q): H is
-    checked on short horizons elsewhere; here the end metric is checked - the training RMSE of
-    the fit against the oracle's RMSE on sampled rows is statistical, so the solve is verified
+    checked on short horizons in test_gpu_hidden.py and at full Q, against the oracle's own fit and
+    its float32 yardstick, in test_gpu_chaos_parity.py; here, at larger N, the solve is verified
     through properties that hold at any size (normal-equation residual, RMSE recomputed in
-    float64 from the returned beta, oracle solve on a row subset of the GPU's H).
+    float64 from the returned beta, oracle solve on a row subset of the GPU's H) and the
+    distribution of H through per-column moments on sampled rows.
 """
 import numpy as np
 import pytest
@@ -100,8 +101,13 @@ def test_fit_gated_configs_properties(elm, name, N, mode):
     Xs = np.lib.stride_tricks.sliding_window_view(series, (cfg.Q, cfg.d))[samp, 0]
     Ho = ocells.hidden(cfg.cell, Xs, W, U, b)
     Hg = res.H[torch.from_numpy(samp).cuda()].cpu().numpy().astype(np.float64)
-    assert np.abs(Ho.mean(0) - Hg.mean(0)).max() < 0.1
-    assert np.abs(Ho.std(0) - Hg.std(0)).max() < 0.1
+    # Bound from the sample size: were the two evaluations of a column independent draws of one
+    # distribution (the worst case: trajectories fully decorrelated), their means over n rows would differ
+    # by sqrt(2 / n) standard deviations and their standard deviations by 1 / sqrt(n) of one; five times
+    # that covers the largest of L columns.  (Full-window error quantiles: tests/test_gpu_chaos_parity.py.)
+    ns, sd = len(samp), Ho.std(0)
+    assert np.all(np.abs(Ho.mean(0) - Hg.mean(0)) <= 5.0 * np.sqrt(2.0 / ns) * sd)
+    assert np.all(np.abs(Ho.std(0) - Hg.std(0)) <= 5.0 * sd / np.sqrt(ns))
     if name == "cfg3":
         # mild amplification only: the sampled rows' error under the fitted beta agrees, and the
         # oracle's own end-to-end fit (its H, its solve) gives the same training RMSE
