@@ -20,6 +20,7 @@
 
 #include "internal.h"
 #include "tsqr_fold.h"
+#include "tsqr_fold_tw.h"
 
 namespace elm {
 namespace {
@@ -44,8 +45,19 @@ struct FoldArgs {
 
 // BR = rows per folded block (64 or 128).  Taller blocks halve the number of sequential
 // Householder steps per input row; they are used whenever the block fits in LDS.
-template <int BR, bool ONE_PANEL = false>
-__global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(const FoldArgs a) {
+// Which fold a kernel variant runs:
+//   kOnePanel  np == 32: four waves, no T factor and no trailing update, three work-groups per compute unit;
+//   kFourWave  four waves, 512 registers each: the 128-row blocks, whose trailing update keeps 144 registers
+//              of reflector operands and would spill in the 256 registers that five waves leave each one;
+//   kTWave     five waves, the T factor built by the fifth while the chain runs (fold_block_tw): the 64-row
+//              blocks, i.e. every width of more than 288 columns (10 % faster there than kFourWave).
+enum FoldMode { kOnePanel = 0, kFourWave = 1, kTWave = 2 };
+
+template <int BR, int MODE>
+__global__ __launch_bounds__(MODE == kTWave ? kThreadsTW : kThreads, MODE == kOnePanel ? 3 : 1)
+void tsqr_fold_kernel(const FoldArgs a) {
+    constexpr int kT = MODE == kTWave ? kThreadsTW : kThreads;  // threads of the work-group
+    constexpr int kW = kT / 64;                                 // ... and waves
     extern __shared__ __align__(16) float lds[];
     const int np = a.np, ldb = a.ldb;
     float* Bs = lds;                           // [BR][ldb], then the scratch areas of fold_block
@@ -57,7 +69,7 @@ __global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(
     int blk_begin, blk_end, per_r = 1;
     if (!a.combine) {
         if (!a.keep)
-            for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
+            for (int idx = tid; idx < np * np; idx += kT) R[idx] = 0.0f;
         blk_begin = (int)(((int64_t)a.nblocks * blockIdx.x) / gridDim.x);
         blk_end = (int)(((int64_t)a.nblocks * (blockIdx.x + 1)) / gridDim.x);
     } else {
@@ -65,7 +77,7 @@ __global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(
         const int r_begin = blockIdx.x * kFan;
         const int r_end = min(r_begin + kFan, a.nprev);
         const float* first = a.src0 + (size_t)r_begin * np * np;
-        for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = first[idx];
+        for (int idx = tid; idx < np * np; idx += kT) R[idx] = first[idx];
         blk_begin = (r_begin + 1) * per_r;
         blk_end = r_end * per_r;
     }
@@ -92,7 +104,7 @@ __global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(
             constexpr int U = 8;
             const bool vec4 = ((nc0 & 3) == 0) && ((ld0 & 3) == 0) &&
                               ((reinterpret_cast<uintptr_t>(src0) & 15) == 0);
-            for (int rb = wave * U; rb < BR; rb += 4 * U) {
+            for (int rb = wave * U; rb < BR; rb += kW * U) {
                 if (vec4) {
                     for (int c = lane * 4; c < nc0; c += 256) {
                         float4 v[U];
@@ -134,11 +146,14 @@ __global__ __launch_bounds__(kThreads, ONE_PANEL ? 3 : 1) void tsqr_fold_kernel(
         }
         __syncthreads();
 
-        fold_block<BR, ONE_PANEL>(R, lds, np, ldb, p0);
+        if constexpr (MODE == kTWave) fold_block_tw<BR>(R, lds, np, ldb, p0);
+        else fold_block<BR, MODE == kOnePanel>(R, lds, np, ldb, p0);
     }
 }
 
-size_t fold_lds_bytes(int np, int br) { return fold::lds_floats(np, br) * sizeof(float); }
+size_t fold_lds_bytes(int np, int br) {
+    return (np > 32 && br == 64 ? fold::lds_floats_tw(np, br) : fold::lds_floats(np, br)) * sizeof(float);
+}
 
 }  // namespace
 
@@ -182,6 +197,7 @@ struct FoldLaunch {
     void (*kern)(const FoldArgs);
     int br;
     size_t lds;
+    int threads;
 };
 
 hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl) {
@@ -198,12 +214,13 @@ hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl)
         // a 32 x 32 triangular input is one 32-row block: the shortest Householder steps
         fl->br = 32;
         fl->lds = fold_lds_bytes(pl.np, 32);
-        fl->kern = tsqr_fold_kernel<32, true>;
+        fl->kern = tsqr_fold_kernel<32, kOnePanel>;
     } else if (pl.np == 32) {
-        fl->kern = tall ? tsqr_fold_kernel<128, true> : tsqr_fold_kernel<64, true>;
+        fl->kern = tall ? tsqr_fold_kernel<128, kOnePanel> : tsqr_fold_kernel<64, kOnePanel>;
     } else {
-        fl->kern = tall ? tsqr_fold_kernel<128> : tsqr_fold_kernel<64>;
+        fl->kern = tall ? tsqr_fold_kernel<128, kFourWave> : tsqr_fold_kernel<64, kTWave>;
     }
+    fl->threads = (pl.np > 32 && !tall) ? kThreadsTW : kThreads;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
 }
@@ -227,7 +244,7 @@ hipError_t launch_tsqr_level0(const SolvePlan& pl, const float* H, const float* 
     a.nblocks = (int)((rows + fl.br - 1) / fl.br);
     a.combine = 0; a.nprev = 0; a.keep = keep;
     a.Rout = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_R[0]);
-    hipLaunchKernelGGL(fl.kern, dim3(pl.groups[0]), dim3(kThreads), fl.lds, stream, a);
+    hipLaunchKernelGGL(fl.kern, dim3(pl.groups[0]), dim3(fl.threads), fl.lds, stream, a);
     return hipGetLastError();
 }
 
@@ -247,7 +264,7 @@ hipError_t launch_tsqr_combine(const SolvePlan& pl, void* ws, float** R_final, h
         a.src0 = reinterpret_cast<const float*>(base + pl.off_R[(lvl - 1) & 1]);
         a.nprev = pl.groups[lvl - 1];
         a.Rout = reinterpret_cast<float*>(base + pl.off_R[lvl & 1]);
-        hipLaunchKernelGGL(fl.kern, dim3(pl.groups[lvl]), dim3(kThreads), fl.lds, stream, a);
+        hipLaunchKernelGGL(fl.kern, dim3(pl.groups[lvl]), dim3(fl.threads), fl.lds, stream, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         *R_final = a.Rout;

@@ -43,7 +43,7 @@ def test_host_layout_code_is_clean_under_asan_and_ubsan(tmp_path):
                    stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
     objs.append(str(tmp_path / "fatbin_stubs.o"))
     exe = str(tmp_path / "layout_driver")
-    link = subprocess.run([HIPCC, "-fsanitize=address", "-fsanitize=undefined", "-o", exe, *objs],
+    link = subprocess.run([HIPCC, "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, *objs],
                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert link.returncode == 0, link.stdout[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:halt_on_error=1",
