@@ -284,10 +284,16 @@ int elm_rnn_predict(const elm_rnn_model* model, const float* X, int64_t ldx_n, i
  * as against its published peaks (the paper reports speed-ups only; this is measurement support, not
  * part of the method): TFLOP/s of a register-resident loop of float32 32x32x2 and of fp16 32x32x16 matrix
  * instructions (the two that step (2) is built on; 1,024 work-groups, four accumulators per wave), and
- * GB/s (read + written) of a streaming copy of half the workspace onto the other half.  workspace: device,
- * at least elm_rnn_probe_workspace_bytes() (2 GiB), contents destroyed.  Synchronises the stream. */
+ * GB/s (read + written) of a streaming copy of half the workspace onto the other half.
+ * valu_overlap_f32 / valu_overlap_f16 (nullable): how much of a vector-ALU loop is hidden behind a loop of
+ * float32 / fp16 matrix instructions that another wave runs on the same SIMD (two waves per SIMD, each loop
+ * timed alone and both together; 1 = the two overlap completely, 0 = one waits for the other): this decides
+ * whether point-wise work can be hidden behind a contraction by giving it waves of its own.
+ * workspace: device, at least elm_rnn_probe_workspace_bytes() (2 GiB), contents destroyed.  Synchronises the
+ * stream. */
 size_t elm_rnn_probe_workspace_bytes(void);
 int elm_rnn_probe_ceilings(double* mfma_f32_tflops, double* mfma_f16_tflops, double* copy_gbs,
+                           double* valu_overlap_f32, double* valu_overlap_f16,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 

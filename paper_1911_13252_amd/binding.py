@@ -110,7 +110,7 @@ def load_library():
     lib.elm_rnn_predict.argtypes = [vp, vp, i64, i64, i64, vp, vp, sz, vp]
     lib.elm_rnn_probe_workspace_bytes.argtypes = []
     lib.elm_rnn_probe_workspace_bytes.restype = sz
-    lib.elm_rnn_probe_ceilings.argtypes = [C.POINTER(C.c_double)] * 3 + [vp, sz, vp]
+    lib.elm_rnn_probe_ceilings.argtypes = [C.POINTER(C.c_double)] * 5 + [vp, sz, vp]
     lib.elm_rnn_strerror.argtypes = [C.c_int]
     lib.elm_rnn_strerror.restype = C.c_char_p
     lib.elm_rnn_last_hip_error.restype = C.c_char_p
@@ -422,10 +422,11 @@ def probe_ceilings(stream=None) -> dict:
     import torch
     lib = load_library()
     ws = torch.empty(int(lib.elm_rnn_probe_workspace_bytes()), dtype=torch.uint8, device="cuda")
-    f32, f16, gbs = C.c_double(), C.c_double(), C.c_double()
-    _check(lib.elm_rnn_probe_ceilings(C.byref(f32), C.byref(f16), C.byref(gbs), ws.data_ptr(), ws.numel(),
-                                      _stream_ptr(stream)))
-    return {"mfma_f32_tflops": f32.value, "mfma_f16_tflops": f16.value, "hbm_copy_gbs": gbs.value}
+    f32, f16, gbs, o32, o16 = (C.c_double() for _ in range(5))
+    _check(lib.elm_rnn_probe_ceilings(C.byref(f32), C.byref(f16), C.byref(gbs), C.byref(o32), C.byref(o16),
+                                      ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return {"mfma_f32_tflops": f32.value, "mfma_f16_tflops": f16.value, "hbm_copy_gbs": gbs.value,
+            "valu_overlap_with_mfma_f32": o32.value, "valu_overlap_with_mfma_f16": o16.value}
 
 
 def predict(model: Model, X, workspace=None, stream=None):

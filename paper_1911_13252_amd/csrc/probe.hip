@@ -59,6 +59,42 @@ __global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ sr
 
 constexpr int kWgs = 1024;      // four work-groups of four waves per compute unit
 
+// Do vector-ALU work and matrix instructions of two waves on one SIMD run at the same time?  Eight waves per
+// work-group, two per SIMD: waves 0-3 run `valu_iters` rounds of sixteen independent multiply-adds, waves
+// 4-7 `mfma_iters` dependent matrix instructions (MODE as above).  Timed alone (the other count zero) and
+// together: together = max of the two means they overlap, together = sum means they exclude each other.
+template <int MODE>
+__global__ __launch_bounds__(512) void coexec_kernel(const float* __restrict__ in, float* __restrict__ out,
+                                                     int valu_iters, int mfma_iters) {
+    const int wave = threadIdx.x >> 6;
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = in[(threadIdx.x + 64 * i) & 1023];
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    if (wave < 4) {
+        for (int it = 0; it < valu_iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = fmaf(x[i], 1.0001f, 0.5f);
+        }
+    } else if (MODE == 0) {
+        for (int it = 0; it < mfma_iters; ++it) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[0], x[1], acc, 0, 0, 0);
+    } else {
+        halfx8 a, b;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[i] = (_Float16)x[i];
+            b[i] = (_Float16)x[i + 8];
+        }
+        for (int it = 0; it < mfma_iters; ++it) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += x[i] + acc[i];
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 }  // namespace
 }  // namespace elm
 
@@ -67,6 +103,7 @@ using namespace elm;
 extern "C" size_t elm_rnn_probe_workspace_bytes(void) { return (size_t)2 << 30; }
 
 extern "C" int elm_rnn_probe_ceilings(double* mfma_f32_tflops, double* mfma_f16_tflops, double* copy_gbs,
+                                      double* valu_overlap_f32, double* valu_overlap_f16,
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (mfma_f32_tflops == nullptr || mfma_f16_tflops == nullptr || copy_gbs == nullptr) return ELM_EINVAL;
     if (workspace == nullptr || workspace_bytes < elm_rnn_probe_workspace_bytes()) return ELM_EWORKSPACE;
@@ -115,6 +152,28 @@ extern "C" int elm_rnn_probe_ceilings(double* mfma_f32_tflops, double* mfma_f16_
         float4* dst = static_cast<float4*>(workspace) + half;
         e = timed([&] { hipLaunchKernelGGL(copy_kernel, dim3(8192), dim3(256), 0, stream, src, dst, half); }, &ms);
         if (e == hipSuccess) *copy_gbs = 2.0 * half * sizeof(float4) / (ms * 1e-3) / 1e9;
+    }
+    // overlap of vector work with the matrix instructions of another wave of the same SIMD: the share of the
+    // shorter of the two loops that is hidden when both run together (1 = they overlap, 0 = one waits)
+    for (int mode = 0; mode < 2 && e == hipSuccess; ++mode) {
+        double* dst = mode == 0 ? valu_overlap_f32 : valu_overlap_f16;
+        if (dst == nullptr) continue;
+        const int vi = 20000, mi = mode == 0 ? 30000 : 60000;      // about 2e6 cycles each
+        float t[3] = {0.0f, 0.0f, 0.0f};
+        const int counts[3][2] = {{vi, 0}, {0, mi}, {vi, mi}};
+        for (int c = 0; c < 3 && e == hipSuccess; ++c) {
+            e = timed([&] {
+                if (mode == 0)
+                    hipLaunchKernelGGL(coexec_kernel<0>, dim3(256), dim3(512), 0, stream, in, out, counts[c][0], counts[c][1]);
+                else
+                    hipLaunchKernelGGL(coexec_kernel<1>, dim3(256), dim3(512), 0, stream, in, out, counts[c][0], counts[c][1]);
+            }, &t[c]);
+        }
+        if (e == hipSuccess) {
+            const double shorter = t[0] < t[1] ? t[0] : t[1];
+            double ov = (t[0] + t[1] - t[2]) / shorter;
+            *dst = ov < 0.0 ? 0.0 : ov > 1.0 ? 1.0 : ov;
+        }
     }
     if (e != hipSuccess) {
         set_hip_error(e, "ceilings probe");

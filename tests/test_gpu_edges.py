@@ -135,7 +135,12 @@ def test_ceilings_probe_reports_plausible_rates(elm):
     assert 80.0 < c["mfma_f32_tflops"] <= 157.3 * 1.02
     assert 1000.0 < c["mfma_f16_tflops"] <= 2500.0 * 1.02
     assert 2000.0 < c["hbm_copy_gbs"] <= 8000.0 * 1.02
+    # float32 matrix instructions keep the vector ALU of their SIMD busy (no overlap with another wave's
+    # vector work), fp16 ones do not: the reason stage 2's chain and trailing update cannot be overlapped
+    # by wave specialisation, and stage 1's gate math cannot hide behind its float32 contraction
+    assert c["valu_overlap_with_mfma_f32"] < 0.25
+    assert c["valu_overlap_with_mfma_f16"] > 0.6
     lib = elm.load_library()
     import ctypes as C
     x = C.c_double()
-    assert lib.elm_rnn_probe_ceilings(C.byref(x), C.byref(x), C.byref(x), None, 0, None) == -2
+    assert lib.elm_rnn_probe_ceilings(C.byref(x), C.byref(x), C.byref(x), None, None, None, 0, None) == -2
