@@ -5,7 +5,7 @@ A "step" is one whole fit (weights from the seed -> hidden matrix H(Q) -> TSQR s
 refinement) over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--contraction fp32]
-                    [--no-fast-mode] [--no-streamed] [--no-ceilings] [--no-cpu-baseline]
+                    [--no-fast-mode] [--no-streamed] [--no-ceilings] [--no-cpu-baseline] [--no-configs]
 
 The reported line is for --contraction (default fp32: float32 matrix instructions, the arithmetic the
 configurations name).  Unless --no-fast-mode is given, the same K steps are then timed once more
@@ -15,7 +15,10 @@ fp16 matrix instructions, float32-equivalent accuracy) and reported under "fast_
 stored) is timed as well and reported under "streamed_fit".
 
 Workload: the LSTM N = 4M, Q = 100, d = 8, L = 512, m = 2 configuration (the one the headline
-metric is quoted on); other configurations can be selected for study with --config.
+metric is quoted on); other configurations can be selected for study with --config.  Unless
+--no-configs is given, the default run also times the other four benchmark configurations (at most
+three fits each) and reports them under "configs": per-stage times, samples/s, the roofline
+fraction of stage 1 and of stage 2 (against both of its ceilings) and the oracle baseline.
 """
 from __future__ import annotations
 
