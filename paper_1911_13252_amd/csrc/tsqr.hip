@@ -47,11 +47,10 @@ struct FoldArgs {
 // Householder steps per input row; they are used whenever the block fits in LDS.
 // Which fold a kernel variant runs:
 //   kOnePanel  np == 32: four waves, no T factor and no trailing update, three work-groups per compute unit;
-//   kFourWave  four waves, 512 registers each: the 128-row blocks, whose trailing update keeps 144 registers
-//              of reflector operands and would spill in the 256 registers that five waves leave each one;
-//   kTWave     five waves, the T factor built by the fifth while the chain runs (fold_block_tw): the 64-row
-//              blocks, i.e. every width of more than 288 columns (10 % faster there than kFourWave).
-enum FoldMode { kOnePanel = 0, kFourWave = 1, kTWave = 2 };
+//   kTWave     every wider matrix: five waves, the T factor built by the fifth while the chain runs
+//              (fold_block_tw; 10 % faster than the four-wave fold_block on 64-row blocks at 544 columns, 2 - 4 %
+//              on 128-row blocks, where a wave's 256 registers hold only half of the update's operands).
+enum FoldMode { kOnePanel = 0, kTWave = 2 };
 
 template <int BR, int MODE>
 __global__ __launch_bounds__(MODE == kTWave ? kThreadsTW : kThreads, MODE == kOnePanel ? 3 : 1)
@@ -152,7 +151,7 @@ void tsqr_fold_kernel(const FoldArgs a) {
 }
 
 size_t fold_lds_bytes(int np, int br) {
-    return (np > 32 && br == 64 ? fold::lds_floats_tw(np, br) : fold::lds_floats(np, br)) * sizeof(float);
+    return (np > 32 ? fold::lds_floats_tw(np, br) : fold::lds_floats(np, br)) * sizeof(float);
 }
 
 }  // namespace
@@ -218,9 +217,9 @@ hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl)
     } else if (pl.np == 32) {
         fl->kern = tall ? tsqr_fold_kernel<128, kOnePanel> : tsqr_fold_kernel<64, kOnePanel>;
     } else {
-        fl->kern = tall ? tsqr_fold_kernel<128, kFourWave> : tsqr_fold_kernel<64, kTWave>;
+        fl->kern = tall ? tsqr_fold_kernel<128, kTWave> : tsqr_fold_kernel<64, kTWave>;
     }
-    fl->threads = (pl.np > 32 && !tall) ? kThreadsTW : kThreads;
+    fl->threads = (pl.np > 32) ? kThreadsTW : kThreads;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
 }

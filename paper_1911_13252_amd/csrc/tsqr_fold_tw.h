@@ -42,9 +42,10 @@ template <int BR>
 __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds, int np, int ldb, int p0) {
     constexpr int RPT = BR / 8;      // rows of a panel column held by one lane
     constexpr int MT = BR / 32;      // 32-row accumulator tiles per block
-    // two waves share a SIMD, so a wave has 256 registers: enough for blocks of 64 rows, whose trailing update
-    // keeps 80 registers of reflector and T operands (128-row blocks need 144 and stay with fold_block)
-    static_assert(BR <= 64, "fold_block_tw: blocks of at most 64 rows");
+    // Two waves share a SIMD, so a wave has 256 registers.  The trailing update of a 64-row block keeps the
+    // panel's reflectors as operands of both of its products in registers (64) next to T (16); a 128-row block
+    // would need 128 + 16, so it keeps those of the first product (64) and reads those of the last from LDS.
+    constexpr bool kCacheV3 = BR <= 64;
     const int NP = np / kNB;
     float* Bs = lds;                           // [BR][ldb]
     float* Gt = Bs + ((BR * ldb + 3) & ~3);    // [32][36]: row k = v_j . v_k for the finished reflectors j < k
@@ -122,14 +123,16 @@ __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds,
             // ================= trailing update on the matrix instruction =================
             {
                 const int c = lane & 31;
-                float va1[BR / 2], va3[MT][16], tq[16];
+                float va1[BR / 2], va3[kCacheV3 ? MT : 1][16], tq[16];
 #pragma unroll
                 for (int s = 0; s < BR / 2; ++s) va1[s] = Bs[(2 * s + half) * ldb + kp + c];
+                if (kCacheV3) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+                    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                    for (int q = 0; q < 16; ++q)
-                        va3[mt][q] = Bs[(mt * 32 + c) * ldb + kp + rho(q) + 4 * half];
+                        for (int q = 0; q < 16; ++q)
+                            va3[kCacheV3 ? mt : 0][q] = Bs[(mt * 32 + c) * ldb + kp + rho(q) + 4 * half];
+                }
 #pragma unroll
                 for (int q = 0; q < 16; ++q) tq[q] = Ts[(rho(q) + 4 * half) * kTsTW + c];
 
@@ -168,8 +171,11 @@ __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds,
                         for (int q = 0; q < 16; ++q)
                             cb[q] = Bs[(mt * 32 + rho(q) + 4 * half) * ldb + cc];
 #pragma unroll
-                        for (int q = 0; q < 16; ++q)
-                            cb = __builtin_amdgcn_mfma_f32_32x32x2f32(va3[mt][q], acc2[q], cb, 0, 0, 0);
+                        for (int q = 0; q < 16; ++q) {
+                            const float a = kCacheV3 ? va3[kCacheV3 ? mt : 0][q]
+                                                     : Bs[(mt * 32 + c) * ldb + kp + rho(q) + 4 * half];
+                            cb = __builtin_amdgcn_mfma_f32_32x32x2f32(a, acc2[q], cb, 0, 0, 0);
+                        }
 #pragma unroll
                         for (int q = 0; q < 16; ++q)
                             Bs[(mt * 32 + rho(q) + 4 * half) * ldb + cc] = cb[q];

@@ -47,6 +47,9 @@ SHAPES = [  # N, Q, d, L  (several tiles, ragged tails, every chunk count, awkwa
     # enough tiles to fill the chip, so the launcher keeps 64-row blocks per wave: narrow layers whose
     # waves split the rows (one and two column blocks), a three-block layer, a ragged last tile
     (70001, 3, 2, 20), (40001, 3, 1, 50), (20000, 2, 3, 90), (16500, 2, 2, 130),
+    # the widths between two and four column blocks (65 to 128 units: three or four 32-column blocks, the last one
+    # partly padding), each with a ragged last tile, at a small and at a chip-filling number of windows
+    (171, 4, 2, 65), (203, 3, 1, 80), (301, 4, 1, 100), (97, 3, 4, 112), (17001, 2, 1, 65), (17003, 2, 2, 112),
 ]
 
 
