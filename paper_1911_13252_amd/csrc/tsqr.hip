@@ -21,6 +21,7 @@
 #include "internal.h"
 #include "tsqr_fold.h"
 #include "tsqr_fold_tw.h"
+#include "tsqr_fold_rr.h"
 
 namespace elm {
 namespace {
@@ -150,6 +151,52 @@ void tsqr_fold_kernel(const FoldArgs a) {
     }
 }
 
+// The same level-0 / combine fold with most of the block in registers (fold_block_rr): 128-row blocks (MT = 4)
+// for the widths whose 128-row block does not fit LDS.
+template <int MT>
+__global__ __launch_bounds__(kThreads, 1)
+void tsqr_fold_rr_kernel(const FoldArgs a) {
+    constexpr int BR = 32 * MT;
+    extern __shared__ __align__(16) float lds[];
+    const int np = a.np;
+    const int tid = threadIdx.x;
+    float* R = a.Rout + (size_t)blockIdx.x * np * np;
+
+    int blk_begin, blk_end, per_r = 1;
+    if (!a.combine) {
+        if (!a.keep)
+            for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = 0.0f;
+        blk_begin = (int)(((int64_t)a.nblocks * blockIdx.x) / gridDim.x);
+        blk_end = (int)(((int64_t)a.nblocks * (blockIdx.x + 1)) / gridDim.x);
+    } else {
+        per_r = (np + BR - 1) / BR;
+        const int r_begin = blockIdx.x * kFan;
+        const int r_end = min(r_begin + kFan, a.nprev);
+        const float* first = a.src0 + (size_t)r_begin * np * np;
+        for (int idx = tid; idx < np * np; idx += kThreads) R[idx] = first[idx];
+        blk_begin = (r_begin + 1) * per_r;
+        blk_end = r_end * per_r;
+    }
+    __syncthreads();
+
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        BlockSource b;
+        int p0 = 0;
+        if (!a.combine) {
+            b.src0 = a.src0; b.ld0 = a.ld0; b.nc0 = a.nc0;
+            b.src1 = a.src1; b.ld1 = a.ld1; b.nc1 = a.nc1;
+            b.row_first = (int64_t)blk * BR; b.row_limit = a.nrows;
+        } else {
+            const int ri = blk / per_r, slice = blk - ri * per_r;
+            b.src0 = a.src0 + (size_t)ri * np * np; b.ld0 = np; b.nc0 = np;
+            b.src1 = nullptr; b.ld1 = 0; b.nc1 = 0;
+            b.row_first = (int64_t)slice * BR; b.row_limit = np;
+            p0 = (slice * BR) / kNB;                            // columns left of the slice are zero
+        }
+        fold_block_rr<MT>(R, b, lds, np, p0);
+    }
+}
+
 size_t fold_lds_bytes(int np, int br) {
     return (np > 32 ? fold::lds_floats_tw(np, br) : fold::lds_floats(np, br)) * sizeof(float);
 }
@@ -161,8 +208,9 @@ SolvePlan make_solve_plan(int64_t N, int L, int m, int level0_groups) {
     pl.N = N; pl.L = L; pl.m = m;
     pl.n = L + m;
     pl.np = (pl.n + 31) / 32 * 32;
-    // 128-row blocks when the padded width allows it (LDS) and there are enough rows for them
-    pl.block_rows = (fold_lds_bytes(pl.np, 128) <= 160 * 1024 && N >= 128 * 64) ? 128 : 64;
+    // 128-row blocks when there are enough rows for them (in LDS if the padded width allows it, else in
+    // registers)
+    pl.block_rows = (N >= 128 * 64) ? 128 : 64;
     const int64_t nblocks = (N + pl.block_rows - 1) / pl.block_rows;
     int64_t g0 = (nblocks + 3) / 4;
     if (g0 < 1) g0 = 1;
@@ -205,10 +253,22 @@ hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl)
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
     if (e != hipSuccess) return e;
-    // 128-row blocks whenever they fit in LDS and the input is tall enough to keep the grid busy
-    const bool tall = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max && pl.block_rows == 128;
+    // 128-row blocks whenever the input is tall enough to keep the grid busy: in LDS if they fit there, else
+    // in registers
+    const bool fits = fold_lds_bytes(pl.np, 128) <= (size_t)lds_max;
+    const bool tall = fits && pl.block_rows == 128;
     fl->br = tall ? 128 : 64;
     fl->lds = fold_lds_bytes(pl.np, fl->br);
+    fl->threads = (pl.np > 32) ? kThreadsTW : kThreads;
+    if (!fits && pl.block_rows == 128) {
+        fl->br = 128;
+        fl->lds = fold::lds_floats_rr(pl.np, 128) * sizeof(float);
+        if (fl->lds > (size_t)lds_max) return hipErrorInvalidValue;      // np <= 544 fits; the library admits no more
+        fl->threads = kThreads;
+        fl->kern = tsqr_fold_rr_kernel<4>;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
+    }
     if (pl.np == 32 && combine) {
         // a 32 x 32 triangular input is one 32-row block: the shortest Householder steps
         fl->br = 32;
@@ -219,7 +279,6 @@ hipError_t fold_launch_config(const SolvePlan& pl, bool combine, FoldLaunch* fl)
     } else {
         fl->kern = tall ? tsqr_fold_kernel<128, kTWave> : tsqr_fold_kernel<64, kTWave>;
     }
-    fl->threads = (pl.np > 32) ? kThreadsTW : kThreads;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(fl->kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)fl->lds);
 }

@@ -38,6 +38,49 @@ __host__ __device__ inline size_t lds_floats(int np, int br) {
     return (size_t)((br * (np + 1) + 3) & ~3) + 32 * kGs + 32 * kTs + 2 * 4 * 32 + 32;
 }
 
+// The triangular factor T of the compact-WY form Q = I - V T V^T of one panel, from
+// T^-1 = diag(1/tau) + striu(V^T V): column j of T by back substitution, one lane per column (32 lanes of one
+// wave call it with their column j); t[l] = 0 for l > j makes every lane run the same instruction stream.
+// Gs: [32][kGs], entry (i, l) = v_i . v_l for i < l; taus: [32]; Ts: [32][kTs], written.
+__device__ __forceinline__ void t_factor_backsubst(const float* Gs, const float* taus, float* Ts, int j) {
+    float t[32], tv[32];
+#pragma unroll
+    for (int l = 0; l < 32; ++l) {
+        tv[l] = taus[l];
+        t[l] = (l == j) ? tv[l] : 0.0f;
+    }
+    // Row i of the Gram matrix is read in 16-byte pieces starting at the multiple of four at
+    // or below i + 1 (the entries at or left of the diagonal in the first piece are skipped);
+    // row i - 1 is requested before row i is used, so the LDS latency hides behind the FMAs.
+    float4 gq[2][8];
+#pragma unroll
+    for (int c = 7; c < 8; ++c) gq[0][c] = *reinterpret_cast<const float4*>(Gs + 30 * kGs + 4 * c);
+#pragma unroll
+    for (int i = 30; i >= 0; --i) {
+        const int cur = (30 - i) & 1;
+        if (i > 0) {
+#pragma unroll
+            for (int c = (i >> 2); c < 8; ++c)        // chunks of row i - 1: from i / 4
+                gq[cur ^ 1][c] = *reinterpret_cast<const float4*>(Gs + (i - 1) * kGs + 4 * c);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;      // four short dependency chains
+#pragma unroll
+        for (int c = ((i + 1) >> 2); c < 8; ++c) {
+            const float4 gv = gq[cur][c];
+            const int l4 = 4 * c;
+            if (l4 + 0 > i) s0 = fmaf(gv.x, t[l4 + 0], s0);
+            if (l4 + 1 > i) s1 = fmaf(gv.y, t[l4 + 1], s1);
+            if (l4 + 2 > i) s2 = fmaf(gv.z, t[l4 + 2], s2);
+            if (l4 + 3 > i) s3 = fmaf(gv.w, t[l4 + 3], s3);
+        }
+        t[i] = (i < j) ? -tv[i] * ((s0 + s1) + (s2 + s3)) : t[i];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) Ts[i * kTs + j] = t[i];
+}
+
 // R: this work-group's np x np upper-triangular factor (global memory); lds: the block at lds[0 .. BR*ldb)
 // followed by the scratch areas; p0: first panel that can be non-zero in the block (columns left of it
 // are zero).  All 256 threads call it; it ends with a barrier.
@@ -136,46 +179,7 @@ __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, in
         for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(kp + kNB + k) * np + kp + kNB + j];
 
         // ================= T factor =================
-        // T^-1 = diag(1/tau) + striu(V^T V): column k of T by back substitution, one lane per
-        // column; t[l] = 0 for l > k makes every lane run the same instruction stream.
-        if (wave == 0 && half == 0) {
-            float t[32], tv[32];
-#pragma unroll
-            for (int l = 0; l < 32; ++l) {
-                tv[l] = taus[l];
-                t[l] = (l == j) ? tv[l] : 0.0f;
-            }
-            // Row i of the Gram matrix is read in 16-byte pieces starting at the multiple of four at
-            // or below i + 1 (the entries at or left of the diagonal in the first piece are skipped);
-            // row i - 1 is requested before row i is used, so the LDS latency hides behind the FMAs.
-            float4 gq[2][8];
-#pragma unroll
-            for (int c = 7; c < 8; ++c) gq[0][c] = *reinterpret_cast<const float4*>(Gs + 30 * kGs + 4 * c);
-#pragma unroll
-            for (int i = 30; i >= 0; --i) {
-                const int cur = (30 - i) & 1;
-                if (i > 0) {
-#pragma unroll
-                    for (int c = (i >> 2); c < 8; ++c)        // chunks of row i - 1: from i / 4
-                        gq[cur ^ 1][c] = *reinterpret_cast<const float4*>(Gs + (i - 1) * kGs + 4 * c);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;      // four short dependency chains
-#pragma unroll
-                for (int c = ((i + 1) >> 2); c < 8; ++c) {
-                    const float4 gv = gq[cur][c];
-                    const int l4 = 4 * c;
-                    if (l4 + 0 > i) s0 = fmaf(gv.x, t[l4 + 0], s0);
-                    if (l4 + 1 > i) s1 = fmaf(gv.y, t[l4 + 1], s1);
-                    if (l4 + 2 > i) s2 = fmaf(gv.z, t[l4 + 2], s2);
-                    if (l4 + 3 > i) s3 = fmaf(gv.w, t[l4 + 3], s3);
-                }
-                t[i] = (i < j) ? -tv[i] * ((s0 + s1) + (s2 + s3)) : t[i];
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int i = 0; i < 32; ++i) Ts[i * kTs + j] = t[i];
-        }
+        if (wave == 0 && half == 0) t_factor_backsubst(Gs, taus, Ts, j);
         __syncthreads();
 
         // ================= trailing update on MFMA =================

@@ -51,6 +51,9 @@ def check_against_oracle(elm, H, T, beta_rtol):
 @pytest.mark.parametrize("N,L,m", [
     (64, 8, 1), (100, 31, 2), (1000, 33, 1), (777, 64, 3), (5000, 100, 1), (3001, 129, 2),
     (20000, 260, 4), (9000, 512, 2), (70000, 96, 1), (600, 511, 16),
+    # widths whose 128-row block does not fit LDS: twelve column tiles in registers, the rest in LDS (none at
+    # 289 + 1 columns ... five at 512 + 16), ragged last block, single and several targets
+    (8192, 289, 1), (16500, 330, 4), (12345, 384, 16), (33000, 448, 1), (8200, 496, 16),
 ])
 def test_solve_matches_oracle(elm, N, L, m):
     H, T = make_system(N, L, m, seed=N + L)
