@@ -452,7 +452,7 @@ __device__ __forceinline__ void hidden_tile(const HiddenArgs& p, const int64_t t
             lds[s * ldb + L + c] = (c < p.m && row < p.N) ? p.T[row * p.m + c] : 0.0f;
         }
         __syncthreads();
-        fold::fold_block<S>(p.Rout + (size_t)blockIdx.x * np * np, lds, np, ldb, 0);
+        fold::fold_block<S>(p.Rout + (size_t)blockIdx.x * np * np, lds, np, ldb, 0, L + p.m);
         return;
     }
 

@@ -40,6 +40,7 @@ struct FoldArgs {
     int nprev;           // combine: number of R factors in the previous stack
     int combine;         // 0 / 1
     int keep;            // level 0: fold into the R factors already in Rout (a later chunk of rows)
+    int nreal;           // columns of [H | T]; the rest of np is zero padding
     float* Rout;         // [gridDim.x][np][np]
     int np, ldb;
 };
@@ -146,8 +147,8 @@ void tsqr_fold_kernel(const FoldArgs a) {
         }
         __syncthreads();
 
-        if constexpr (MODE == kTWave) fold_block_tw<BR>(R, lds, np, ldb, p0);
-        else fold_block<BR, MODE == kOnePanel>(R, lds, np, ldb, p0);
+        if constexpr (MODE == kTWave) fold_block_tw<BR>(R, lds, np, ldb, p0, a.nreal);
+        else fold_block<BR, MODE == kOnePanel>(R, lds, np, ldb, p0, a.nreal);
     }
 }
 
@@ -179,22 +180,10 @@ void tsqr_fold_rr_kernel(const FoldArgs a) {
     }
     __syncthreads();
 
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
-        BlockSource b;
-        int p0 = 0;
-        if (!a.combine) {
-            b.src0 = a.src0; b.ld0 = a.ld0; b.nc0 = a.nc0;
-            b.src1 = a.src1; b.ld1 = a.ld1; b.nc1 = a.nc1;
-            b.row_first = (int64_t)blk * BR; b.row_limit = a.nrows;
-        } else {
-            const int ri = blk / per_r, slice = blk - ri * per_r;
-            b.src0 = a.src0 + (size_t)ri * np * np; b.ld0 = np; b.nc0 = np;
-            b.src1 = nullptr; b.ld1 = 0; b.nc1 = 0;
-            b.row_first = (int64_t)slice * BR; b.row_limit = np;
-            p0 = (slice * BR) / kNB;                            // columns left of the slice are zero
-        }
-        fold_block_rr<MT>(R, b, lds, np, p0);
-    }
+    FoldInput in;
+    in.src0 = a.src0; in.src1 = a.src1; in.ld0 = a.ld0; in.ld1 = a.ld1; in.nc0 = a.nc0; in.nc1 = a.nc1;
+    in.nrows = a.nrows; in.combine = a.combine; in.per_r = per_r; in.np = np; in.nreal = a.nreal;
+    fold_blocks_rr<MT>(R, in, blk_begin, blk_end, lds, np);
 }
 
 size_t fold_lds_bytes(int np, int br) {
@@ -301,6 +290,7 @@ hipError_t launch_tsqr_level0(const SolvePlan& pl, const float* H, const float* 
     a.nrows = rows;
     a.nblocks = (int)((rows + fl.br - 1) / fl.br);
     a.combine = 0; a.nprev = 0; a.keep = keep;
+    a.nreal = pl.n;
     a.Rout = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_R[0]);
     hipLaunchKernelGGL(fl.kern, dim3(pl.groups[0]), dim3(fl.threads), fl.lds, stream, a);
     return hipGetLastError();
@@ -318,6 +308,7 @@ hipError_t launch_tsqr_combine(const SolvePlan& pl, void* ws, float** R_final, h
     a.ldb = pl.np + 1;
     a.ld0 = pl.np; a.nc0 = pl.np;
     a.combine = 1;
+    a.nreal = pl.n;
     for (int lvl = 1; lvl < pl.levels; ++lvl) {
         a.src0 = reinterpret_cast<const float*>(base + pl.off_R[(lvl - 1) & 1]);
         a.nprev = pl.groups[lvl - 1];

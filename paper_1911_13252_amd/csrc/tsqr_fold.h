@@ -38,6 +38,94 @@ __host__ __device__ inline size_t lds_floats(int np, int br) {
     return (size_t)((br * (np + 1) + 3) & ~3) + 32 * kGs + 32 * kTs + 2 * 4 * 32 + 32;
 }
 
+// Barrier between the column steps of a chain: orders LDS traffic only (nothing in global memory changes hands
+// inside a chain), so loads from global memory stay in flight across it
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+enum ChainFlags {
+    kChainPublish = 1,      // tau and the Gram entries of the reflectors go to LDS (for the T factor)
+    kChainGramByStep = 2,   // Gram entry (j, k) is stored at [k][j] (a row per step) instead of [j][k]
+};
+
+// The Householder chain of one 32-column panel of [R; B]: `steps` column steps (32, or fewer when the rest of
+// the panel is zero padding), run by the 256 threads of four waves.
+//   pv[RPT]   lane (j, g) holds rows RPT g .. RPT g + RPT-1 of panel column j of the block (j = thread % 32,
+//             g = thread / 32); replaced by the reflectors v (below the implicit unit entry in R)
+//   rdv[32]   column j of the panel's diagonal block of R (every g holds a copy); replaced by the new one
+//   red       [2][32][4] floats of LDS for the cross-wave sums;  G [32][kGs], taus [32]: see ChainFlags
+// One reduction per step gives the norm of column k and its dot products with every column.  The two
+// half-waves of a wave hold different rows, so column k arrives as two scalars per register (lanes k and
+// 32 + k); every lane uses both as scalar operands: the dot product is taken with each and the own half's sum
+// selected once, and the update adds the other half's term with a zero coefficient.  A finished column keeps
+// its unscaled entries x (its coefficient is zero from its own step on) and is scaled to the reflector
+// v = x f once, after the last step, by an exactly rounded product (the stored reflector must not lose
+// digits); the Gram entries carry both factors.  Columns whose remaining mass is below 1e-30 get the identity
+// reflector: they only arise as rounding residue when a block has fewer rows than columns, and the hardware
+// square root and reciprocal (1 ulp: a reflector built from them is orthogonal to float32 rounding) flush
+// denormals; what those make of such a column is dropped by selects, not branched around.
+template <int RPT, int FLAGS>
+__device__ __forceinline__ void panel_chain(float (&pv)[RPT], float (&rdv)[32], int steps, float* red, float* G,
+                                            float* taus, int wave, int j, int g, int half) {
+    float f_own = 0.0f;
+    auto step = [&](const int k) {
+        float lo[RPT], hi[RPT];
+        float s_lo = 0.0f, s_hi = 0.0f;
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            lo[i] = lane_bcast(pv[i], k);
+            hi[i] = lane_bcast(pv[i], 32 + k);
+            s_lo = fmaf(lo[i], pv[i], s_lo);
+            s_hi = fmaf(hi[i], pv[i], s_hi);
+        }
+        float s = half ? s_hi : s_lo;
+        s += other_half(s, half);
+        float* rb = red + (k & 1) * 128;            // [32 columns][4 waves]
+        if (half == 0) rb[4 * j + wave] = s;
+        const float x0 = lane_bcast(rdv[k], k);     // every copy is identical
+        lds_barrier();
+        const float4 pj = *reinterpret_cast<const float4*>(rb + 4 * j);
+        const float4 pk = *reinterpret_cast<const float4*>(rb + 4 * k);
+        const float sj = (pj.x + pj.y) + (pj.z + pj.w);
+        const float sigma = (pk.x + pk.y) + (pk.z + pk.w);
+        const float nrm2 = fmaf(x0, x0, sigma);
+        const bool live = sigma > 0.0f && nrm2 > 1e-30f;
+        const float nrm = __builtin_amdgcn_sqrtf(nrm2);
+        const float alpha_l = (x0 >= 0.0f) ? -nrm : nrm;
+        const float alpha = live ? alpha_l : x0;
+        const float tau = live ? (alpha_l - x0) * __builtin_amdgcn_rcpf(alpha_l) : 0.0f;
+        const float f = live ? __builtin_amdgcn_rcpf(x0 - alpha_l) : 0.0f;
+        // lanes j > k apply the reflector, lane j == k stores alpha
+        const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
+        rdv[k] = (j == k) ? alpha : rdv[k] - w;
+        const float cf = -(f * w);                  // zero for the columns at and left of k
+        const float cf_lo = half ? 0.0f : cf, cf_hi = half ? cf : 0.0f;
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) pv[i] = fmaf(hi[i], cf_hi, fmaf(lo[i], cf_lo, pv[i]));
+        if ((FLAGS & kChainPublish) && g == 0) {
+            if (j == k) taus[k] = tau;
+            // v_j . v_k for the finished reflector j
+            if (j < k) G[(FLAGS & kChainGramByStep) ? k * kGs + j : j * kGs + k] = (f * f_own) * sj;
+        }
+        f_own = (j == k) ? f : f_own;
+    };
+    // (two copies of the unrolled steps: a per-step test in the common case would end every step's basic block
+    // and keep the compiler from overlapping neighbouring steps)
+    if (steps >= 32) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) step(k);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+            if (k < steps) step(k);
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) pv[i] *= f_own;
+}
+
 // The triangular factor T of the compact-WY form Q = I - V T V^T of one panel, from
 // T^-1 = diag(1/tau) + striu(V^T V): column j of T by back substitution, one lane per column (32 lanes of one
 // wave call it with their column j); t[l] = 0 for l > j makes every lane run the same instruction stream.
@@ -83,11 +171,12 @@ __device__ __forceinline__ void t_factor_backsubst(const float* Gs, const float*
 
 // R: this work-group's np x np upper-triangular factor (global memory); lds: the block at lds[0 .. BR*ldb)
 // followed by the scratch areas; p0: first panel that can be non-zero in the block (columns left of it
-// are zero).  All 256 threads call it; it ends with a barrier.
+// are zero); nreal: columns of the matrix proper (the rest of np is zero padding, for which the last panel
+// takes no steps).  All 256 threads call it; it ends with a barrier.
 // ONE_PANEL: np == 32, the whole width is one panel: no T factor, no trailing update, and far fewer
 // registers, so that several work-groups share a compute unit.
 template <int BR, bool ONE_PANEL = false>
-__device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, int np, int ldb, int p0) {
+__device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, int np, int ldb, int p0, int nreal) {
     constexpr int RPT = BR / 8;      // rows of a panel column held by one lane
     constexpr int MT = BR / 32;      // 32-row accumulator tiles per block
     const int NP = np / kNB;
@@ -115,53 +204,7 @@ __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, in
 #pragma unroll
         for (int i = 0; i < RPT; ++i) pv[i] = Bs[(RPT * g + i) * ldb + kp + j];
 
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            // column k of this lane's row group: broadcast from lane k (lower half-wave) or
-            // 32 + k (upper half-wave) through scalar registers
-            float xk[RPT];
-            float s = 0.0f;
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-                const float lo = lane_bcast(pv[i], k);
-                const float hi = lane_bcast(pv[i], 32 + k);
-                xk[i] = half ? hi : lo;
-                s = fmaf(xk[i], pv[i], s);
-            }
-            s += other_half(s, half);
-            float* rb = red + (k & 1) * 128;
-            if (half == 0) rb[wave * 32 + j] = s;
-            const float x0 = lane_bcast(rdv[k], k);     // every copy is identical
-            __syncthreads();
-            const float sj = (rb[j] + rb[32 + j]) + (rb[64 + j] + rb[96 + j]);
-            const float sigma = (rb[k] + rb[32 + k]) + (rb[64 + k] + rb[96 + k]);
-            float alpha = x0, tau = 0.0f, f = 0.0f;
-            const float nrm2 = fmaf(x0, x0, sigma);
-            // Columns whose remaining mass is below 1e-30 are left alone (identity reflector):
-            // they arise as rounding residue of residue when a block has fewer rows than
-            // columns, and the hardware sqrt / reciprocal flush denormals.
-            if (sigma > 0.0f && nrm2 > 1e-30f) {
-                // hardware sqrt / reciprocal (1 ulp): a reflector built from slightly rounded
-                // tau and 1/(x0 - alpha) is orthogonal to the same order as float32 rounding
-                const float nrm = __builtin_amdgcn_sqrtf(nrm2);
-                alpha = (x0 >= 0.0f) ? -nrm : nrm;
-                tau = (alpha - x0) * __builtin_amdgcn_rcpf(alpha);
-                f = __builtin_amdgcn_rcpf(x0 - alpha);
-            }
-            // branch-free update: lanes j > k apply the reflector, lane j == k stores it
-            const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
-            rdv[k] = (j == k) ? alpha : rdv[k] - w;
-            // one select and one multiply-add for both roles: the reflector's own column becomes xk f
-            // (exactly rounded: the stored reflector must not lose digits), every column right of it
-            // pv - xk f w, the columns left of it keep pv (w = 0)
-            const float cf = (j == k) ? f : -(f * w);
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, (j == k) ? 0.0f : pv[i]);
-            if (!ONE_PANEL && g == 0) {
-                if (j == k) taus[k] = tau;
-                if (j < k) Gs[j * kGs + k] = f * sj;      // v_j . v_k for the finished reflector j
-            }
-        }
+        panel_chain<RPT, ONE_PANEL ? 0 : kChainPublish>(pv, rdv, nreal - kp, red, Gs, taus, wave, j, g, half);
         if (!ONE_PANEL) {                 // the trailing update reads the reflectors from the block
 #pragma unroll
             for (int i = 0; i < RPT; ++i) Bs[(RPT * g + i) * ldb + kp + j] = pv[i];

@@ -2,18 +2,19 @@
 // to [H | T] a block of rows at a time), for matrices too wide for a 128-row block in LDS: most of the block
 // lives in REGISTERS, in the accumulator layout of the 32x32 matrix instruction.
 //
-// A compute unit has 512 KB of vector registers against 160 KB of LDS.  Four waves hold the first twelve
-// 32-column tiles of a 128-row block in their accumulation registers (wave w owns tiles w, w + 4, w + 8; a tile
-// is MT 32x32 accumulators; with Y and W that fills the 256 accumulation registers, the only place the compiler
-// puts an accumulator operand), the remaining tiles (five at 544 columns) stay in LDS.  Against the 64-row
-// block that fits LDS as a whole at more than 288 columns this halves the number of Householder column steps
-// per input row and the traffic of the R factor.  Both products of the trailing update take a register tile
-// where it is: an accumulator register holds rows r and r + 4 of the tile in its two half-waves, which is
-// exactly a B operand of the matrix instruction for the k-slot (r, r + 4), and C_B -= V_B W accumulates in
-// place.  An LDS tile is read into vector registers in the same layout, enters both products as a B operand,
-// and is written back after a vector add of the second product.  The panel being factored is staged in LDS
-// (the owner of a register tile writes it there before the chain; an LDS tile is factored where it is), and the
-// reflectors that replace it serve as A operands.
+// A compute unit has 512 KB of vector registers against 160 KB of LDS.  Four waves hold the LAST twelve
+// 32-column tiles of a 128-row block in their accumulation registers (a tile is MT 32x32 accumulators; three
+// tiles, Y and W fill the 256 accumulation registers, the only place the compiler puts an accumulator
+// operand), the first tiles (five at 544 columns) stay in LDS.  A tile is updated by every panel left of it,
+// so the last twelve of seventeen tiles take 126 of the 136 tile updates of a block.  Against the 64-row block
+// that fits LDS as a whole at more than 288 columns this halves the number of Householder column steps per
+// input row and the traffic of the R factor.  Both products of the trailing update take a register tile where
+// it is: an accumulator register holds rows r and r + 4 of the tile in its two half-waves, which is exactly a
+// B operand of the matrix instruction for the k-slot (r, r + 4), and C_B -= V_B W accumulates in place.  An LDS
+// tile is read into vector registers in the same layout, enters both products as a B operand, and is written
+// back after a vector add of the second product.  The panel being factored is staged in LDS (the owner of a
+// register tile writes it there right after it has updated it for the panel before; an LDS tile is factored
+// where it is), and the reflectors that replace it serve as A operands.
 //
 // The T factor is a serial back substitution of one half-wave.  It runs on the wave that owns tile p, which
 // has one tile less to update than the busiest wave in three panels out of four, and the other waves start
@@ -29,14 +30,14 @@ namespace fold {
 
 constexpr int kLdp = 33;           // row stride of a tile in LDS
 constexpr int kSlotsRR = 3;        // register tiles per wave
-constexpr int kRegTilesRR = 4 * kSlotsRR;
+constexpr int kRegTilesRR = 4 * kSlotsRR;        // the last twelve tiles of a block
 
 __host__ __device__ inline int lds_tiles_rr(int np) { return np / kNB > kRegTilesRR ? np / kNB - kRegTilesRR : 0; }
 
-// LDS floats: the staged panel and the LDS tiles (BR x 32 each, row stride 33), the Gram matrix, the T factor,
-// cross-wave partial sums, tau
+// LDS floats: two staging areas for the panels of register tiles and the LDS tiles (BR x 32 each, row stride
+// 33), the Gram matrix, the T factor, cross-wave partial sums, tau
 __host__ __device__ inline size_t lds_floats_rr(int np, int br) {
-    return (size_t)(1 + lds_tiles_rr(np)) * ((br * kLdp + 3) & ~3) + 32 * kGs + 32 * kTs + 2 * 4 * 32 + 32;
+    return (size_t)(2 + lds_tiles_rr(np)) * ((br * kLdp + 3) & ~3) + 32 * kGs + 32 * kTs + 2 * 4 * 32 + 32;
 }
 
 // Where the rows of a block come from: columns [0, nc0) from src0, [nc0, nc0 + nc1) from src1, zero beyond;
@@ -49,25 +50,81 @@ struct BlockSource {
     int64_t row_first, row_limit;
 };
 
-// One 32-column tile of the block (all zero unless valid) in the accumulator layout: register q of
-// accumulator mt holds row 32 mt + rho(q) + 4 half, column lane % 32.
-template <int MT>
-__device__ __forceinline__ void load_tile_rr(floatx16 (&t)[MT], const BlockSource& b, int tile, bool valid,
-                                             int lane) {
-    const int c = lane & 31, half = lane >> 5;
-    const int col = tile * kNB + c;
-    const bool from0 = col < b.nc0;
-    const bool colok = valid && col < b.nc0 + b.nc1;
-    const float* base = from0 ? b.src0 + col : b.src1 + (col - b.nc0);
-    const int64_t ld = from0 ? b.ld0 : b.ld1;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int64_t row = b.row_first + mt * 32 + rho(q) + 4 * half;
-            t[mt][q] = (colok && row < b.row_limit) ? base[row * ld] : 0.0f;
-        }
+// What a launch folds: the rows of [src0 | src1] in blocks of BR (level 0), or BR-row slices of the np x np
+// factors of the previous level (combine; per_r slices per factor).
+struct FoldInput {
+    const float* src0;
+    const float* src1;
+    int64_t ld0, ld1;
+    int nc0, nc1;
+    int64_t nrows;
+    int combine, per_r, np;
+    int nreal;      // columns of the matrix proper, the rest of np is zero padding
+};
+
+// Block blk of the input, and the first panel that can be non-zero in it
+template <int BR>
+__device__ __forceinline__ void block_source_rr(const FoldInput& in, int blk, BlockSource* b, int* p0) {
+    if (!in.combine) {
+        b->src0 = in.src0; b->ld0 = in.ld0; b->nc0 = in.nc0;
+        b->src1 = in.src1; b->ld1 = in.ld1; b->nc1 = in.nc1;
+        b->row_first = (int64_t)blk * BR; b->row_limit = in.nrows;
+        *p0 = 0;
+    } else {
+        const int ri = blk / in.per_r, slice = blk - ri * in.per_r;
+        b->src0 = in.src0 + (size_t)ri * in.np * in.np; b->ld0 = in.np; b->nc0 = in.np;
+        b->src1 = nullptr; b->ld1 = 0; b->nc1 = 0;
+        b->row_first = (int64_t)slice * BR; b->row_limit = in.np;
+        *p0 = (slice * BR) / kNB;                           // columns left of the slice are zero
+    }
 }
+
+// The rows of one block behind two buffer descriptors (base addresses in scalar registers, 32-bit lane offsets;
+// loads beyond the block's last valid row return zero through the descriptor's range check, and so do the lanes
+// of columns that belong to the other source or to neither, whose offsets start beyond every range).
+struct BlockLoader {
+    __amdgpu_buffer_rsrc_t rs0, rs1;
+    unsigned row0, row1;      // bytes per row of either source
+    int nc0, nc1;
+    static constexpr unsigned kNowhere = 0x80000000u;
+
+    template <int BR>
+    __device__ __forceinline__ void open(const BlockSource& b) {
+        int64_t rows = b.row_limit - b.row_first;
+        rows = rows < 0 ? 0 : (rows > BR ? BR : rows);
+        row0 = (unsigned)b.ld0 * 4u;
+        row1 = (unsigned)b.ld1 * 4u;
+        nc0 = b.nc0;
+        nc1 = b.nc1;
+        rs0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(b.src0 + b.row_first * b.ld0), 0,
+                                                (int)(rows * row0), 0x00020000);
+        rs1 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(b.nc1 > 0 ? b.src1 + b.row_first * b.ld1 : b.src0), 0,
+            b.nc1 > 0 ? (int)(rows * row1) : 0, 0x00020000);
+    }
+
+    // One 32-column tile of the block (all zero unless valid) in the accumulator layout: register q of
+    // accumulator mt holds row 32 mt + rho(q) + 4 half, column lane % 32.
+    template <int MT>
+    __device__ __forceinline__ void load_tile(floatx16 (&t)[MT], int tile, bool valid, int lane) const {
+        const int c = lane & 31, half = lane >> 5;
+        const int col = tile * kNB + c;
+        const bool in0 = valid && col < nc0;
+        const bool in1 = valid && col >= nc0 && col < nc0 + nc1;
+        const unsigned v0 = in0 ? (unsigned)(4 * half) * row0 + (unsigned)col * 4u : kNowhere;
+        const unsigned v1 = in1 ? (unsigned)(4 * half) * row1 + (unsigned)(col - nc0) * 4u : kNowhere;
+        const bool any1 = valid && tile * kNB + kNB > nc0 && nc1 > 0;      // wave-uniform
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const unsigned r = (unsigned)(mt * 32 + rho(q));
+                unsigned bits = __builtin_amdgcn_raw_buffer_load_b32(rs0, v0 + r * row0, 0, 0);
+                if (any1) bits |= __builtin_amdgcn_raw_buffer_load_b32(rs1, v1 + r * row1, 0, 0);
+                t[mt][q] = __builtin_bit_cast(float, bits);
+            }
+    }
+};
 
 // Trailing update of one 32-column tile with the panel's reflectors V_B (Vp, BR x 32, row stride 33) and
 // factor T (Ts):
@@ -107,7 +164,7 @@ __device__ __forceinline__ void update_tile_rr(floatx16 (&cbt)[MT], const bool i
         __builtin_amdgcn_sched_barrier(0);
     }
     if (!synced) {
-        __syncthreads();        // T is complete
+        lds_barrier();          // T is complete
         synced = true;
     }
     float tq[16], y[16], w[16];
@@ -157,21 +214,19 @@ __device__ __forceinline__ void update_tile_rr(floatx16 (&cbt)[MT], const bool i
     }
 }
 
-// Loads the block (tiles p0 .. NP-1; the ones left of p0 are zero in the source and never touched) and folds it.
-// R: this work-group's np x np upper-triangular factor (global memory); lds: lds_floats_rr(np, 32 MT) floats;
-// p0: first panel that can be non-zero in the block.  All 256 threads call it; it ends with a barrier.
-// np <= 32 (12 + 5): the LDS tiles of wider matrices would not fit.
+// The barriers inside a block order LDS traffic only: the R factor needs no ordering there, because inside a
+// block every element of it is touched by one lane only, and the barrier that ends a block is a full one.
 template <int MT>
-__device__ __forceinline__ void fold_block_rr(float* __restrict__ R, const BlockSource& src, float* lds, int np,
-                                              int p0) {
+__device__ __forceinline__ void fold_blocks_rr(float* __restrict__ R, const FoldInput& in, int blk_begin,
+                                               int blk_end, float* lds, int np) {
     constexpr int BR = 32 * MT;
     constexpr int RPT = BR / 8;      // rows of a panel column held by one lane during the chain
     constexpr int kTile = (BR * kLdp + 3) & ~3;
     const int NP = np / kNB;
-    const int NL = lds_tiles_rr(np);
-    float* Pb = lds;                           // [BR][33] staged panel of a register tile
-    float* Lt = Pb + kTile;                    // [NL][BR][33] tiles 12 .. NP-1
-    float* Gs = Lt + NL * kTile;               // [32][36] strict upper part of V_B^T V_B
+    const int t0 = lds_tiles_rr(np);           // tiles 0 .. t0-1 live in LDS, t0 .. NP-1 in registers
+    float* Pb = lds;                           // [2][BR][33] staged panels of register tiles (panel p in p & 1)
+    float* Lt = Pb + 2 * kTile;                // [t0][BR][33] the LDS tiles
+    float* Gs = Lt + t0 * kTile;               // [32][36] strict upper part of V_B^T V_B
     float* Ts = Gs + 32 * kGs;                 // [32][33] compact-WY T
     float* red = Ts + 32 * kTs;                // [2][4][32] cross-wave partial sums
     float* taus = red + 2 * 4 * 32;            // [32]
@@ -185,17 +240,34 @@ __device__ __forceinline__ void fold_block_rr(float* __restrict__ R, const Block
     const __amdgpu_buffer_rsrc_t Rrs = __builtin_amdgcn_make_buffer_rsrc(R, 0, np * np * 4, 0x00020000);
     const unsigned rt_lane = (unsigned)(4 * half * np + j) * 4u;
 
+    floatx16 cb[kSlotsRR][MT];       // register tiles of this wave: tiles t0 + wave, + 4, + 8
+    // stage a register tile of this wave as panel pp
+    auto stage = [&](const floatx16 (&tile)[MT], int pp) {
+        float* dst = Pb + (pp & 1) * kTile;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) dst[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tile[mt][q];
+    };
+
+  for (int blk = blk_begin; blk < blk_end; ++blk) {
+    BlockSource src;
+    int p0;
+    block_source_rr<BR>(in, blk, &src, &p0);
+    BlockLoader loader;
+    loader.template open<BR>(src);
+
     // ---- the block: register tiles of this wave, then its LDS tiles (tile t belongs to wave t % 4)
-    floatx16 cb[kSlotsRR][MT];
 #pragma unroll
     for (int i = 0; i < kSlotsRR; ++i) {
-        const int t = wave + 4 * i;
-        load_tile_rr<MT>(cb[i], src, t, t >= p0 && t < NP, lane);
+        const int t = t0 + wave + 4 * i;
+        loader.template load_tile<MT>(cb[i], t, t >= p0 && t < NP, lane);
     }
-    for (int t = kRegTilesRR + wave; t < NP; t += 4) {
+    for (int t = wave; t < t0; t += 4) {
+        if (t < p0) continue;
         floatx16 tl[MT];
-        load_tile_rr<MT>(tl, src, t, t >= p0, lane);
-        float* dst = Lt + (t - kRegTilesRR) * kTile;
+        loader.template load_tile<MT>(tl, t, true, lane);
+        float* dst = Lt + t * kTile;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -207,63 +279,24 @@ __device__ __forceinline__ void fold_block_rr(float* __restrict__ R, const Block
     for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(p0 * kNB + k) * np + p0 * kNB + j];
     for (int p = p0; p < NP; ++p) {
         const int kp = p * kNB;
-        const int ow = p & 3;                  // the wave that owns tile p
-        float* Vp = (p < kRegTilesRR) ? Pb : Lt + (p - kRegTilesRR) * kTile;
-        if (p < kRegTilesRR && wave == ow) {
-            const int io = p >> 2;
+        const bool reg_tile = p >= t0;
+        const int ow = (reg_tile ? p - t0 : p) & 3;     // the wave that owns tile p
+        float* Vp = reg_tile ? Pb + (p & 1) * kTile : Lt + p * kTile;
+        if (p == p0) {
+            // the first panel of a block is staged here, the later ones by their owners during the update before
+            if (reg_tile && wave == ow) {
 #pragma unroll
-            for (int i = 0; i < kSlotsRR; ++i) {
-                if (i == io) {
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int q = 0; q < 16; ++q)
-                            Pb[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = cb[i][mt][q];
-                }
+                for (int i = 0; i < kSlotsRR; ++i)
+                    if (i == ((p - t0) >> 2)) stage(cb[i], p);
             }
+            lds_barrier();
         }
-        __syncthreads();
 
         // ================= panel factorisation (the chain of fold_block) =================
         float pv[RPT];
 #pragma unroll
         for (int i = 0; i < RPT; ++i) pv[i] = Vp[(RPT * g + i) * kLdp + j];
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            float xk[RPT];
-            float s = 0.0f;
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-                const float lo = lane_bcast(pv[i], k);
-                const float hi = lane_bcast(pv[i], 32 + k);
-                xk[i] = half ? hi : lo;
-                s = fmaf(xk[i], pv[i], s);
-            }
-            s += other_half(s, half);
-            float* rb = red + (k & 1) * 128;
-            if (half == 0) rb[wave * 32 + j] = s;
-            const float x0 = lane_bcast(rdv[k], k);
-            lds_barrier();
-            const float sj = (rb[j] + rb[32 + j]) + (rb[64 + j] + rb[96 + j]);
-            const float sigma = (rb[k] + rb[32 + k]) + (rb[64 + k] + rb[96 + k]);
-            float alpha = x0, tau = 0.0f, f = 0.0f;
-            const float nrm2 = fmaf(x0, x0, sigma);
-            if (sigma > 0.0f && nrm2 > 1e-30f) {
-                const float nrm = __builtin_amdgcn_sqrtf(nrm2);
-                alpha = (x0 >= 0.0f) ? -nrm : nrm;
-                tau = (alpha - x0) * __builtin_amdgcn_rcpf(alpha);
-                f = __builtin_amdgcn_rcpf(x0 - alpha);
-            }
-            const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
-            rdv[k] = (j == k) ? alpha : rdv[k] - w;
-            const float cf = (j == k) ? f : -(f * w);
-#pragma unroll
-            for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, (j == k) ? 0.0f : pv[i]);
-            if (g == 0) {
-                if (j == k) taus[k] = tau;
-                if (j < k) Gs[j * kGs + k] = f * sj;      // v_j . v_k for the finished reflector j
-            }
-        }
+        panel_chain<RPT, kChainPublish>(pv, rdv, in.nreal - kp, red, Gs, taus, wave, j, g, half);
 #pragma unroll
         for (int i = 0; i < RPT; ++i) Vp[(RPT * g + i) * kLdp + j] = pv[i];
         if (g == 0) {
@@ -271,7 +304,7 @@ __device__ __forceinline__ void fold_block_rr(float* __restrict__ R, const Block
             for (int k = 0; k < 32; ++k)
                 if (k <= j) R[(size_t)(kp + k) * np + kp + j] = rdv[k];
         }
-        __syncthreads();                    // E1: reflectors in place of the panel; tau and Gram matrix complete
+        lds_barrier();                      // E1: reflectors in place of the panel; tau and Gram matrix complete
         if (p + 1 == NP) break;
         // next panel's diagonal block of R: in flight during the trailing update, which never touches the
         // rows of R that the next panel factors
@@ -285,36 +318,38 @@ __device__ __forceinline__ void fold_block_rr(float* __restrict__ R, const Block
             bool synced = false;
             if (wave == ow) {
                 if (half == 0) t_factor_backsubst(Gs, taus, Ts, j);
-                __syncthreads();                // E2
+                lds_barrier();                  // E2
                 synced = true;
             }
 #pragma unroll
             for (int i = 0; i < kSlotsRR; ++i) {
-                const int ct = wave + 4 * i;
-                if (ct > p && ct < NP)
+                const int ct = t0 + wave + 4 * i;
+                if (ct > p && ct < NP) {
                     update_tile_rr<MT>(cb[i], true, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts, j,
                                        half, synced);
+                    if (ct == p + 1) stage(cb[i], ct);     // the next panel
+                }
             }
-            for (int ct = kRegTilesRR + wave; ct < NP; ct += 4) {
+            for (int ct = wave; ct < t0; ct += 4) {
                 if (ct <= p) continue;
-                float* tile = Lt + (ct - kRegTilesRR) * kTile;
+                float* tile = Lt + ct * kTile;
                 floatx16 tl[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int q = 0; q < 16; ++q) tl[mt][q] = tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j];
-                update_tile_rr<MT>(tl, false, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts, j, half,
-                                   synced);
+                update_tile_rr<MT>(tl, false, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts, j, half, synced);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int q = 0; q < 16; ++q) tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tl[mt][q];
             }
-            if (!synced) __syncthreads();       // E2
+            if (!synced) lds_barrier();         // E2
         }
-        __syncthreads();                    // E3: the staging area is free for the next panel
+        lds_barrier();                      // E3: the next panel is staged, this one's reflectors are dead
     }
-    __syncthreads();
+    __syncthreads();                        // R and the LDS tiles change hands between blocks
+  }
 }
 
 }  // namespace fold

@@ -28,18 +28,12 @@ __host__ __device__ inline size_t lds_floats_tw(int np, int br) {
     return (size_t)((br * (np + 1) + 3) & ~3) + 32 * kGs + 32 * kTsTW + 2 * 4 * 32 + 32;
 }
 
-// Barrier of the column steps: orders LDS traffic only (nothing in global memory changes hands inside a chain)
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 // R: this work-group's np x np upper-triangular factor (global memory); lds: the block at lds[0 .. BR*ldb)
-// followed by the scratch areas (lds_floats_tw); p0: first panel that can be non-zero in the block.
+// followed by the scratch areas (lds_floats_tw); p0: first panel that can be non-zero in the block; nreal:
+// columns of the matrix proper (the last panel takes no steps for the zero padding beyond them).
 // All 320 threads call it; it ends with a barrier.
 template <int BR>
-__device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds, int np, int ldb, int p0) {
+__device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds, int np, int ldb, int p0, int nreal) {
     constexpr int RPT = BR / 8;      // rows of a panel column held by one lane
     constexpr int MT = BR / 32;      // 32-row accumulator tiles per block
     // Two waves share a SIMD, so a wave has 256 registers.  The trailing update of a 64-row block keeps the
@@ -69,42 +63,7 @@ __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds,
             float pv[RPT];
 #pragma unroll
             for (int i = 0; i < RPT; ++i) pv[i] = Bs[(RPT * g + i) * ldb + kp + j];
-#pragma unroll
-            for (int k = 0; k < 32; ++k) {
-                float xk[RPT];
-                float s = 0.0f;
-#pragma unroll
-                for (int i = 0; i < RPT; ++i) {
-                    const float lo = lane_bcast(pv[i], k);
-                    const float hi = lane_bcast(pv[i], 32 + k);
-                    xk[i] = half ? hi : lo;
-                    s = fmaf(xk[i], pv[i], s);
-                }
-                s += other_half(s, half);
-                float* rb = red + (k & 1) * 128;
-                if (half == 0) rb[wave * 32 + j] = s;
-                const float x0 = lane_bcast(rdv[k], k);
-                lds_barrier();
-                const float sj = (rb[j] + rb[32 + j]) + (rb[64 + j] + rb[96 + j]);
-                const float sigma = (rb[k] + rb[32 + k]) + (rb[64 + k] + rb[96 + k]);
-                float alpha = x0, tau = 0.0f, f = 0.0f;
-                const float nrm2 = fmaf(x0, x0, sigma);
-                if (sigma > 0.0f && nrm2 > 1e-30f) {
-                    const float nrm = __builtin_amdgcn_sqrtf(nrm2);
-                    alpha = (x0 >= 0.0f) ? -nrm : nrm;
-                    tau = (alpha - x0) * __builtin_amdgcn_rcpf(alpha);
-                    f = __builtin_amdgcn_rcpf(x0 - alpha);
-                }
-                const float w = (j > k) ? tau * fmaf(f, sj, rdv[k]) : 0.0f;
-                rdv[k] = (j == k) ? alpha : rdv[k] - w;
-                const float cf = (j == k) ? f : -(f * w);
-#pragma unroll
-                for (int i = 0; i < RPT; ++i) pv[i] = fmaf(xk[i], cf, (j == k) ? 0.0f : pv[i]);
-                if (g == 0) {
-                    if (j == k) taus[k] = tau;
-                    if (j < k) Gt[k * kGs + j] = f * sj;      // v_j . v_k for the finished reflector j
-                }
-            }
+            panel_chain<RPT, kChainPublish | kChainGramByStep>(pv, rdv, nreal - kp, red, Gt, taus, wave, j, g, half);
 #pragma unroll
             for (int i = 0; i < RPT; ++i) Bs[(RPT * g + i) * ldb + kp + j] = pv[i];
             if (g == 0) {
@@ -212,7 +171,8 @@ __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds,
                 for (int q = 0; q < kTsTW / 4; ++q)
                     *reinterpret_cast<float4*>(Ts + lane * kTsTW + 4 * q) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
-            for (int k = 0; k < 32; ++k) {
+            const int steps = min(32, nreal - p * kNB);     // one barrier per step of the chain
+            for (int k = 0; k < steps; ++k) {
                 // the chain writes tau and the Gram row of its step k-2 between the barriers of steps k-2 and
                 // k-1: complete once this wave has passed the barrier of step k-1
                 if (t_lane && k >= 2) t_column(k - 2);
