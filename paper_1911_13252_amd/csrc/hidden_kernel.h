@@ -143,6 +143,14 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
 // three gates) are compiled for two waves per SIMD: one wave's gate math overlaps another's matrix work.
 // FUSE: the finished tile is not stored; together with its rows of T it becomes the next block of the
 // work-group's tall-skinny QR (step 3 of the paper's Algorithm "S-R-ELM" needs H(Q) only through H^+ T).
+
+// The level-0 fold of a finished tile, as a call: the fold's registers are allocated apart from those of the
+// step loop (inlined, the fold's code changed which values of the step loop the compiler spilled, and the
+// headline variant lost 4 %).
+template <int S>
+__device__ __noinline__ void fold_tile(float* R, float* lds, int np, int ldb, int nreal) {
+    fold::fold_block<S>(R, lds, np, ldb, 0, nreal);
+}
 template <int CELL, int MS, int NCH, int STAGE, int WR, bool FUSE>
 __device__ __forceinline__ void hidden_tile(const HiddenArgs& p, const int64_t tile, float* lds) {
     static_assert(WR == 1 || NCH == 1, "rows are split over the waves only when one column chunk exists");
@@ -452,7 +460,13 @@ __device__ __forceinline__ void hidden_tile(const HiddenArgs& p, const int64_t t
             lds[s * ldb + L + c] = (c < p.m && row < p.N) ? p.T[row * p.m + c] : 0.0f;
         }
         __syncthreads();
-        fold::fold_block<S>(p.Rout + (size_t)blockIdx.x * np * np, lds, np, ldb, 0, L + p.m);
+        // (the variants that share a compute unit between two work-groups keep the fold inline: a call would
+        // be compiled for the full register file and halve their occupancy)
+        constexpr bool kTwoPerUnit = MS == 1 && (NCH == 1 || (NCH == 2 && CELL != ELM_CELL_LSTM));
+        if constexpr (kTwoPerUnit)
+            fold::fold_block<S>(p.Rout + (size_t)blockIdx.x * np * np, lds, np, ldb, 0, L + p.m);
+        else
+            fold_tile<S>(p.Rout + (size_t)blockIdx.x * np * np, lds, np, ldb, L + p.m);
         return;
     }
 
