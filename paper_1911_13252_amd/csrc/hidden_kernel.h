@@ -144,6 +144,35 @@ __device__ __forceinline__ void contract(floatx16 (&acc)[G][MS], const float* __
 // FUSE: the finished tile is not stored; together with its rows of T it becomes the next block of the
 // work-group's tall-skinny QR (step 3 of the paper's Algorithm "S-R-ELM" needs H(Q) only through H^+ T).
 
+// The final cell state of a tile (LSTM, for callers that ask for it): element (ms, i) of column chunk ch of
+// this lane is row rbase + 32 ms + 8 (i / 4) + 4 (lane / 32) + i % 4, column 32 (4 ch + wcol) + lane % 32.
+template <int MS, int NCH>
+__device__ __forceinline__ void write_cell_state(float* C, const float* st, int64_t row0, int64_t N, int L, int nJB,
+                                                 int wcol, int rbase, int lane) {
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int jb = ch * 4 + wcol;
+        const int col = jb * 32 + (lane & 31);
+        if (jb < nJB && col < L) {
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = row0 + rbase + ms * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                    if (row < N) C[row * L + col] = st[(ch * MS + ms) * 16 + i];
+                }
+        }
+    }
+}
+// The same as a call, for the variants that run one work-group per compute unit: inlined, these rarely
+// taken stores (128 addresses of 64 bits) made the compiler spill 67 more registers of the headline variant,
+// twelve of them stored in every step of the window loop (30 GB of scratch traffic per launch at full size).
+template <int MS, int NCH>
+__device__ __noinline__ void write_cell_state_call(float* C, const float* st, int64_t row0, int64_t N, int L,
+                                                   int nJB, int wcol, int rbase, int lane) {
+    write_cell_state<MS, NCH>(C, st, row0, N, L, nJB, wcol, rbase, lane);
+}
+
 // The level-0 fold of a finished tile, as a call: the fold's registers are allocated apart from those of the
 // step loop (inlined, the fold's code changed which values of the step loop the compiler spilled, and the
 // headline variant lost 4 %).
@@ -477,19 +506,19 @@ __device__ __forceinline__ void hidden_tile(const HiddenArgs& p, const int64_t t
         if (row < p.N) p.H[row * L + j] = A0[s * R + hoff + slot * L + j];
     }
     if (CELL == ELM_CELL_LSTM && p.C != nullptr) {
+        constexpr bool kTwoPerUnit = MS == 1 && (NCH == 1 || (NCH == 2 && CELL != ELM_CELL_LSTM));
+        if constexpr (kTwoPerUnit) {
+            write_cell_state<MS, NCH>(p.C, &st[0][0][0], row0, p.N, L, p.nJB, wcol, rbase, lane);
+        } else {
+            // a copy, so that the state itself never has an address and stays in registers
+            float tmp[NCH * MS * 16];
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-            const int jb = ch * 4 + wcol;
-            const int col = jb * 32 + col_in;
-            if (jb < p.nJB && col < L) {
+            for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
                 for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int64_t row = row0 + acc_row(ms, i);
-                        if (row < p.N) p.C[row * L + col] = st[ch][ms][i];
-                    }
-            }
+                    for (int i = 0; i < 16; ++i) tmp[(ch * MS + ms) * 16 + i] = st[ch][ms][i];
+            write_cell_state_call<MS, NCH>(p.C, tmp, row0, p.N, L, p.nJB, wcol, rbase, lane);
         }
     }
 }
