@@ -79,7 +79,7 @@ def stage2_roofline(cfg, solve_ms):
     tf = flops / (solve_ms * 1e-3) / 1e12
     gbs = nbytes / (solve_ms * 1e-3) / 1e9
     t_roof_ms = 1e3 * max(flops / (PEAK_FP32_MFMA_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9))
-    return {"kernel": "tsqr_fold_kernel + back-solve + refinement (stage 2)", "solve_ms": solve_ms,
+    return {"kernel": "TSQR fold kernels + back-solve + refinement (stage 2)", "solve_ms": solve_ms,
             "achieved_tflops": tf, "frac_of_fp32_mfma_peak": tf / PEAK_FP32_MFMA_TFLOPS,
             "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS,
             "roofline_ms": t_roof_ms, "frac_of_roofline": t_roof_ms / solve_ms}
