@@ -90,6 +90,7 @@ FUSED_CASES = [  # data, cell, N, L: every stage-1 variant that has the in-kerne
     ("cfg3", "lstm", 5000, 160),      # two column chunks
     ("cfg3", "lstm", 5001, 300),      # three chunks, two-pass with LDS staging
     ("cfg5", "lstm", 4003, 512),      # four chunks (the headline variant)
+    ("cfg5", "lstm", 8300, 512),      # ... with enough rows for the combine levels to fold 128-row slices
     ("cfg5", "elman", 4100, 320),     # three chunks (8 input channels keep the wide layer well conditioned)
     ("cfg5", "elman", 4099, 512),     # four chunks
     ("cfg4", "gru", 4500, 288),       # 64-row tiles
