@@ -30,22 +30,28 @@ hipError_t launch_variant(const HiddenArgs& a, int64_t tiles, size_t lds_bytes, 
     return hipGetLastError();
 }
 
-constexpr int kStage = 24;      // staged values per lane: 24 KB of LDS per work-group
+// staged values per lane (1 KB of LDS per work-group each): 27 where the operand leaves that much room (the
+// headline shape fills LDS to the byte with them), else 24
+constexpr int kStage = 24, kStageMore = 27;
 
 template <int CELL, int MS>
 hipError_t launch_nch(int nch, const HiddenArgs& a, int64_t tiles, size_t lds, size_t lds_max,
                       hipStream_t s) {
     // the two-pass LSTM variants take the LDS staging when the operand leaves room for it
+    constexpr bool kStaged = (CELL == ELM_CELL_LSTM) && MS == 2;
     const size_t staged = lds + (size_t)kStage * kThreads * sizeof(float);
-    const bool stage = (CELL == ELM_CELL_LSTM) && MS == 2 && nch >= 3 && staged <= lds_max;
+    const size_t staged_more = lds + (size_t)kStageMore * kThreads * sizeof(float);
+    const bool stage = kStaged && nch >= 3 && staged <= lds_max;
+    const bool more = stage && staged_more <= lds_max;
     switch (nch) {
         case 1: return launch_variant<CELL, MS, 1, 0>(a, tiles, lds, s);
         case 2: return launch_variant<CELL, MS, 2, 0>(a, tiles, lds, s);
         case 3:
-            if (stage) return launch_variant<CELL, MS, 3, (CELL == ELM_CELL_LSTM && MS == 2) ? kStage : 0>(a, tiles, staged, s);
+            if (stage) return launch_variant<CELL, MS, 3, kStaged ? kStage : 0>(a, tiles, staged, s);
             return launch_variant<CELL, MS, 3, 0>(a, tiles, lds, s);
         case 4:
-            if (stage) return launch_variant<CELL, MS, 4, (CELL == ELM_CELL_LSTM && MS == 2) ? kStage : 0>(a, tiles, staged, s);
+            if (more) return launch_variant<CELL, MS, 4, kStaged ? kStageMore : 0>(a, tiles, staged_more, s);
+            if (stage) return launch_variant<CELL, MS, 4, kStaged ? kStage : 0>(a, tiles, staged, s);
             return launch_variant<CELL, MS, 4, 0>(a, tiles, lds, s);
         default: return hipErrorInvalidValue;
     }
