@@ -48,7 +48,6 @@ def test_host_layout_code_is_clean_under_asan_and_ubsan(tmp_path):
     assert link.returncode == 0, link.stdout[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:halt_on_error=1",
                UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
-    env.pop("LD_PRELOAD", None)          # the sanitizer runtime must come first in the process
     run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=600)
     assert run.returncode == 0, run.stdout[-4000:]
     assert run.stdout.strip().splitlines()[-1].startswith("OK "), run.stdout[-2000:]
