@@ -52,6 +52,17 @@ TRAFFIC_SPLIT_SOURCE = ("profiles/fit_cfg5_split16_kernel_trace_and_pmc.txt: sto
                         "measured by this run")
 
 
+_last_note = [0.0]
+
+
+def note(msg: str) -> None:
+    """Progress on stderr (stdout carries the one JSON line): at most one line per 20 s of wall time."""
+    now = time.perf_counter()
+    if now - _last_note[0] >= 20.0:
+        _last_note[0] = now
+        print(f"bench.py: {msg}", file=sys.stderr, flush=True)
+
+
 def stage1_flops(cfg) -> float:
     """Algorithmic flops of one hidden-matrix launch: 2 Q kL (L + d) per sample for the dense cells,
     2 L (Q (Q - 1) / 2 + Q d) for the paper's diagonal multi-lag Elman, 2 L (L Q (Q - 1) / 2 + Q d) for
@@ -356,14 +367,17 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    note(f"{cfg.name}: inputs resident, {args.warmup} warm-up and {args.steps} timed fits follow")
+    for i in range(args.warmup):
         step()
+        note(f"warm-up fit {i + 1}/{args.warmup} done")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stats, marks = [], [t0]
-    for _ in range(args.steps):
+    for i in range(args.steps):
         stats.append(step())              # a fit synchronises its stream before it returns
         marks.append(time.perf_counter())
+        note(f"timed fit {i + 1}/{args.steps} done")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     per_step_ms = [1e3 * (b - a) for a, b in zip(marks[:-1], marks[1:])]
@@ -403,7 +417,10 @@ def main() -> int:
         step("split16")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        fstats = [step("split16") for _ in range(args.steps)]
+        fstats = []
+        for i in range(args.steps):
+            fstats.append(step("split16"))
+            note(f"split16 fit {i + 1}/{args.steps} done")
         torch.cuda.synchronize()
         fdt = time.perf_counter() - t0
         f_hidden = float(np.mean([s.t_hidden_ms for s in fstats]))
@@ -428,7 +445,10 @@ def main() -> int:
         torch.cuda.synchronize()
         ssteps = min(args.steps, 2)
         t0 = time.perf_counter()
-        sstats = [sstep() for _ in range(ssteps)]
+        sstats = []
+        for i in range(ssteps):
+            sstats.append(sstep())
+            note(f"streamed fit {i + 1}/{ssteps} done")
         torch.cuda.synchronize()
         sdt = time.perf_counter() - t0
         out["streamed_fit"] = {"value": cfg.N * ssteps / sdt, "unit": "samples/s", "steps": ssteps,
@@ -458,10 +478,13 @@ def main() -> int:
         if not args.no_streamed and args.contraction == "fp32":
             del sws
         torch.cuda.empty_cache()
-        out["configs"] = [measure_config(elm, torch, synthdata.get_config(n), min(args.steps, 3),
-                                         0 if args.no_cpu_baseline else cpu_rows[n])
-                          for n in ("cfg1", "cfg2", "cfg3", "cfg4")]
+        out["configs"] = []
+        for n in ("cfg1", "cfg2", "cfg3", "cfg4"):
+            note(f"{n}: fits and oracle baseline")
+            out["configs"].append(measure_config(elm, torch, synthdata.get_config(n), min(args.steps, 3),
+                                                 0 if args.no_cpu_baseline else cpu_rows[n]))
     if not args.no_cpu_baseline:
+        note(f"{cfg.name}: oracle baseline on the host cores")
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_rows or cpu_rows[cfg.name])
     print(json.dumps(out))
     return 0
