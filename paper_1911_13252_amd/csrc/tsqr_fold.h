@@ -183,7 +183,7 @@ __device__ __forceinline__ void fold_block(float* __restrict__ R, float* lds, in
     float* Bs = lds;                           // [BR][ldb]
     float* Gs = Bs + ((BR * ldb + 3) & ~3);    // [32][36] strict upper part of V_B^T V_B
     float* Ts = Gs + 32 * kGs;                 // [32][33] compact-WY T
-    float* red = Ts + 32 * kTs;                // [2][4][32] cross-wave partial sums
+    float* red = Ts + 32 * kTs;                // [2][32][4] cross-wave partial sums
     float* taus = red + 2 * 4 * 32;            // [32]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -228,7 +228,7 @@ __device__ __forceinline__ void fold_blocks_rr(float* __restrict__ R, const Fold
     float* Lt = Pb + 2 * kTile;                // [t0][BR][33] the LDS tiles
     float* Gs = Lt + t0 * kTile;               // [32][36] strict upper part of V_B^T V_B
     float* Ts = Gs + 32 * kGs;                 // [32][33] compact-WY T
-    float* red = Ts + 32 * kTs;                // [2][4][32] cross-wave partial sums
+    float* red = Ts + 32 * kTs;                // [2][32][4] cross-wave partial sums
     float* taus = red + 2 * 4 * 32;            // [32]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -250,106 +250,107 @@ __device__ __forceinline__ void fold_blocks_rr(float* __restrict__ R, const Fold
             for (int q = 0; q < 16; ++q) dst[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tile[mt][q];
     };
 
-  for (int blk = blk_begin; blk < blk_end; ++blk) {
-    BlockSource src;
-    int p0;
-    block_source_rr<BR>(in, blk, &src, &p0);
-    BlockLoader loader;
-    loader.template open<BR>(src);
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        BlockSource src;
+        int p0;
+        block_source_rr<BR>(in, blk, &src, &p0);
+        BlockLoader loader;
+        loader.template open<BR>(src);
 
-    // ---- the block: register tiles of this wave, then its LDS tiles (tile t belongs to wave t % 4)
+        // ---- the block: register tiles of this wave, then its LDS tiles (tile t belongs to wave t % 4)
 #pragma unroll
-    for (int i = 0; i < kSlotsRR; ++i) {
-        const int t = t0 + wave + 4 * i;
-        loader.template load_tile<MT>(cb[i], t, t >= p0 && t < NP, lane);
-    }
-    for (int t = wave; t < t0; t += 4) {
-        if (t < p0) continue;
-        floatx16 tl[MT];
-        loader.template load_tile<MT>(tl, t, true, lane);
-        float* dst = Lt + t * kTile;
+        for (int i = 0; i < kSlotsRR; ++i) {
+            const int t = t0 + wave + 4 * i;
+            loader.template load_tile<MT>(cb[i], t, t >= p0 && t < NP, lane);
+        }
+        for (int t = wave; t < t0; t += 4) {
+            if (t < p0) continue;
+            floatx16 tl[MT];
+            loader.template load_tile<MT>(tl, t, true, lane);
+            float* dst = Lt + t * kTile;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) dst[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tl[mt][q];
-    }
-
-    float rdv[32];
-#pragma unroll
-    for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(p0 * kNB + k) * np + p0 * kNB + j];
-    for (int p = p0; p < NP; ++p) {
-        const int kp = p * kNB;
-        const bool reg_tile = p >= t0;
-        const int ow = (reg_tile ? p - t0 : p) & 3;     // the wave that owns tile p
-        float* Vp = reg_tile ? Pb + (p & 1) * kTile : Lt + p * kTile;
-        if (p == p0) {
-            // the first panel of a block is staged here, the later ones by their owners during the update before
-            if (reg_tile && wave == ow) {
-#pragma unroll
-                for (int i = 0; i < kSlotsRR; ++i)
-                    if (i == ((p - t0) >> 2)) stage(cb[i], p);
-            }
-            lds_barrier();
+                for (int q = 0; q < 16; ++q) dst[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tl[mt][q];
         }
 
-        // ================= panel factorisation (the chain of fold_block) =================
-        float pv[RPT];
+        float rdv[32];
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) pv[i] = Vp[(RPT * g + i) * kLdp + j];
-        panel_chain<RPT, kChainPublish>(pv, rdv, in.nreal - kp, red, Gs, taus, wave, j, g, half);
+        for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(p0 * kNB + k) * np + p0 * kNB + j];
+        for (int p = p0; p < NP; ++p) {
+            const int kp = p * kNB;
+            const bool reg_tile = p >= t0;
+            const int ow = (reg_tile ? p - t0 : p) & 3;     // the wave that owns tile p
+            float* Vp = reg_tile ? Pb + (p & 1) * kTile : Lt + p * kTile;
+            if (p == p0) {
+                // the first panel of a block is staged here, the later ones by their owners during the update before
+                if (reg_tile && wave == ow) {
 #pragma unroll
-        for (int i = 0; i < RPT; ++i) Vp[(RPT * g + i) * kLdp + j] = pv[i];
-        if (g == 0) {
-#pragma unroll
-            for (int k = 0; k < 32; ++k)
-                if (k <= j) R[(size_t)(kp + k) * np + kp + j] = rdv[k];
-        }
-        lds_barrier();                      // E1: reflectors in place of the panel; tau and Gram matrix complete
-        if (p + 1 == NP) break;
-        // next panel's diagonal block of R: in flight during the trailing update, which never touches the
-        // rows of R that the next panel factors
-#pragma unroll
-        for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(kp + kNB + k) * np + kp + kNB + j];
-
-        // ================= T factor and trailing update =================
-        {
-            // Every wave passes E2 exactly once: the owner of tile p after it has built T, the others after the
-            // first product of their first tile (or at the end, if they have no tile).
-            bool synced = false;
-            if (wave == ow) {
-                if (half == 0) t_factor_backsubst(Gs, taus, Ts, j);
-                lds_barrier();                  // E2
-                synced = true;
-            }
-#pragma unroll
-            for (int i = 0; i < kSlotsRR; ++i) {
-                const int ct = t0 + wave + 4 * i;
-                if (ct > p && ct < NP) {
-                    update_tile_rr<MT>(cb[i], true, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts, j,
-                                       half, synced);
-                    if (ct == p + 1) stage(cb[i], ct);     // the next panel
+                    for (int i = 0; i < kSlotsRR; ++i)
+                        if (i == ((p - t0) >> 2)) stage(cb[i], p);
                 }
+                lds_barrier();
             }
-            for (int ct = wave; ct < t0; ct += 4) {
-                if (ct <= p) continue;
-                float* tile = Lt + ct * kTile;
-                floatx16 tl[MT];
+
+            // ================= panel factorisation (the chain of fold_block) =================
+            float pv[RPT];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+            for (int i = 0; i < RPT; ++i) pv[i] = Vp[(RPT * g + i) * kLdp + j];
+            panel_chain<RPT, kChainPublish>(pv, rdv, in.nreal - kp, red, Gs, taus, wave, j, g, half);
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) tl[mt][q] = tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j];
-                update_tile_rr<MT>(tl, false, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts, j, half, synced);
+            for (int i = 0; i < RPT; ++i) Vp[(RPT * g + i) * kLdp + j] = pv[i];
+            if (g == 0) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int q = 0; q < 16; ++q) tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tl[mt][q];
+                for (int k = 0; k < 32; ++k)
+                    if (k <= j) R[(size_t)(kp + k) * np + kp + j] = rdv[k];
             }
-            if (!synced) lds_barrier();         // E2
+            lds_barrier();                      // E1: reflectors in place of the panel; tau and Gram matrix complete
+            if (p + 1 == NP) break;
+            // next panel's diagonal block of R: in flight during the trailing update, which never touches the
+            // rows of R that the next panel factors
+#pragma unroll
+            for (int k = 0; k < 32; ++k) rdv[k] = R[(size_t)(kp + kNB + k) * np + kp + kNB + j];
+
+            // ================= T factor and trailing update =================
+            {
+                // Every wave passes E2 exactly once: the owner of tile p after it has built T, the others after the
+                // first product of their first tile (or at the end, if they have no tile).
+                bool synced = false;
+                if (wave == ow) {
+                    if (half == 0) t_factor_backsubst(Gs, taus, Ts, j);
+                    lds_barrier();                  // E2
+                    synced = true;
+                }
+#pragma unroll
+                for (int i = 0; i < kSlotsRR; ++i) {
+                    const int ct = t0 + wave + 4 * i;
+                    if (ct > p && ct < NP) {
+                        update_tile_rr<MT>(cb[i], true, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp,
+                                           Ts, j, half, synced);
+                        if (ct == p + 1) stage(cb[i], ct);     // the next panel
+                    }
+                }
+                for (int ct = wave; ct < t0; ct += 4) {
+                    if (ct <= p) continue;
+                    float* tile = Lt + ct * kTile;
+                    floatx16 tl[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) tl[mt][q] = tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j];
+                    update_tile_rr<MT>(tl, false, Rrs, rt_lane, (unsigned)(kp * np + ct * kNB) * 4u, np, Vp, Ts,
+                                       j, half, synced);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) tile[(mt * 32 + rho(q) + 4 * half) * kLdp + j] = tl[mt][q];
+                }
+                if (!synced) lds_barrier();         // E2
+            }
+            lds_barrier();                      // E3: the next panel is staged, this one's reflectors are dead
         }
-        lds_barrier();                      // E3: the next panel is staged, this one's reflectors are dead
+        __syncthreads();                        // R and the LDS tiles change hands between blocks
     }
-    __syncthreads();                        // R and the LDS tiles change hands between blocks
-  }
 }
 
 }  // namespace fold

@@ -44,7 +44,7 @@ __device__ __forceinline__ void fold_block_tw(float* __restrict__ R, float* lds,
     float* Bs = lds;                           // [BR][ldb]
     float* Gt = Bs + ((BR * ldb + 3) & ~3);    // [32][36]: row k = v_j . v_k for the finished reflectors j < k
     float* Ts = Gt + 32 * kGs;                 // [32][36] compact-WY T
-    float* red = Ts + 32 * kTsTW;              // [2][4][32] cross-wave partial sums
+    float* red = Ts + 32 * kTsTW;              // [2][32][4] cross-wave partial sums
     float* taus = red + 2 * 4 * 32;            // [32]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
