@@ -60,6 +60,18 @@ def test_solve_matches_oracle(elm, N, L, m):
     check_against_oracle(elm, H, T, beta_rtol=1e-6)
 
 
+@pytest.mark.parametrize("N,L,m", [
+    # either side of every switch between the fold kernels: 8,192 rows (64- or 128-row blocks), 288 padded
+    # columns (128-row block in LDS or in registers), 384 padded columns (no tile or one tile left in LDS),
+    # targets that straddle two column tiles
+    (8191, 287, 1), (8192, 287, 1), (8191, 288, 1), (8192, 288, 1), (8193, 319, 2), (8192, 383, 1),
+    (8192, 384, 1), (8320, 385, 16), (8191, 500, 16), (8192, 500, 16),
+])
+def test_solve_at_the_kernel_selection_boundaries(elm, N, L, m):
+    H, T = make_system(N, L, m, seed=7 * N + L)
+    check_against_oracle(elm, H, T, beta_rtol=1e-6)
+
+
 def test_ill_conditioned_system_meets_the_residual_bar_after_refinement(elm):
     # cond ~ 1e5: a float32 factorisation alone leaves a residual of 1e-4 .. 1e-3
     H, T = make_system(20000, 80, 1, seed=9, cond=1e5, noise=0.02)
