@@ -1,20 +1,22 @@
 // Stage 2a: tall-skinny Householder QR of the augmented matrix [H | T] (the paper's section
 // "Computing beta": H = QR, z = Q^T Y; applying the reflectors to [H | T] yields R and z at once).
 //
-// Every work-group keeps its own upper-triangular R (np x np, global memory, L2 resident) and
-// folds BR-row blocks (64 or 128 rows) of the input into it, one after the other:
-// [R; B] -> [R'; 0].  Because R is triangular, the reflector that eliminates column k only touches row k of R and the whole block,
-// so V = [I; V_B] and one fold costs 2*BR*n^2 flops: no work is spent on the zero triangle.
+// Every work-group keeps its own upper-triangular R (np x np, global memory) and folds BR-row blocks (64 or 128
+// rows) of the input into it, one after the other: [R; B] -> [R'; 0].  Because R is triangular, the reflector
+// that eliminates column k only touches row k of R and the whole block, so V = [I; V_B] and one fold costs
+// 2*BR*n^2 flops: no work is spent on the zero triangle.
 // Per panel of 32 columns:
-//   * panel factorisation on the VALU: lanes hold BR/8 rows of one panel column in registers, the
-//     Householder norm and all dot products of a step come from ONE reduction (wavefront shuffle
-//     inside a wave, a 4-entry LDS exchange across the 4 waves);
+//   * panel factorisation on the VALU (panel_chain in tsqr_fold.h): lanes hold BR/8 rows of one panel column in
+//     registers, the Householder norm and all dot products of a step come from ONE reduction (wavefront shuffle
+//     inside a wave, a 16-byte LDS read across the 4 waves);
 //   * the triangular factor T of the compact-WY form Q = I - V T V^T from the Gram matrix of V_B;
 //   * trailing update of the remaining 32-column tiles on fp32 MFMA:
 //       Y = C_R + V_B^T C_B,  W = T^T Y,  C_R -= W,  C_B -= V_B W
 //     where Y and W never leave the accumulator registers (the MFMA k-slot order is chosen so an
 //     accumulator register can be fed back as a B operand).
-// The R factors of all work-groups are combined by the same kernel in a binary tree: a work-group
+// The block lives in LDS (fold_block, fold_block_tw: up to 288 padded columns at 128 rows) or mostly in
+// registers (fold_blocks_rr: wider matrices).
+// The R factors of all work-groups are combined by the same kernels in a binary tree: a work-group
 // starts from a copy of its first R and folds the row slices of the second one into it (skipping the
 // panels left of each slice of the triangular input), so a level costs one R fold of serial work.
 
